@@ -1,0 +1,114 @@
+/*
+ * attn.h -- C ABI of the MI355X (gfx950) fused attention forward library.
+ *
+ * The operation is the fused scaled-dot-product attention forward pass of the
+ * paper's section 6.1 ("Major Operators": tile staging, score computation,
+ * masking, normalisation, output accumulation), with the two outputs its
+ * appendix C.3 names: the normalised accumulator  O = acc / l  and the
+ * per-row statistic  lse = m + log(l)  (natural logarithm).
+ *
+ *   for every batch b and query head h, kv head g = h / (Hq / Hkv):
+ *     S = scale * Q[b,h] K[b,g]^T ;  S[i][j] = -inf for j > i when causal
+ *     P = softmax over j of S     ;  O[b,h] = P V[b,g]
+ *     lse[b,h,i] = ln sum_j exp(S[i][j])
+ *
+ * Every pointer is a DEVICE pointer unless stated otherwise.  The caller owns
+ * all buffers; the library allocates nothing, keeps no state between calls and
+ * never synchronises the device: work is enqueued on `stream` and the call
+ * returns.  Inputs are never written; `o` and `lse` are fully overwritten.
+ * Calls from several host threads on different streams are safe.
+ *
+ * Layouts (contiguous, row-major, innermost index last):
+ *   q, o : [B, Hq , N, d]        k, v : [B, Hkv, N, d]        lse : [B, Hq, N]
+ * q, k, v, o must be 16-byte aligned, lse 4-byte aligned.
+ *
+ * Errors are reported by return code only (never abort, never throw); all
+ * argument checks run before anything is enqueued.
+ */
+#ifndef ATTN_MI355X_H
+#define ATTN_MI355X_H
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  ATTN_OK = 0,
+  ATTN_ERR_NULL = 1,        /* a required pointer is NULL                         */
+  ATTN_ERR_SHAPE = 2,       /* non-positive size, Hq % Hkv != 0, misaligned ptr   */
+  ATTN_ERR_DTYPE = 3,       /* dtype is not one of attn_dtype                     */
+  ATTN_ERR_UNSUPPORTED = 4, /* valid request this build has no kernel for (d)     */
+  ATTN_ERR_LAUNCH = 5       /* the HIP runtime refused the launch                 */
+} attn_status;
+
+typedef enum {
+  ATTN_BF16 = 0,    /* q,k,v bfloat16; products on bf16 MFMA, fp32 accumulate     */
+  ATTN_FP8_E4M3 = 1 /* q,k,v OCP e4m3 bytes; P re-quantised to e4m3 before PV     */
+} attn_dtype;
+
+/*
+ * attn_fwd -- fused attention forward (section 6.1 phase list; appendix C.3 outputs).
+ *
+ *   q,k,v   device, `dtype` elements, layouts above
+ *   o       device, bfloat16 [B,Hq,N,d] (bf16 output for both input dtypes)
+ *   lse     device, float32  [B,Hq,N], required
+ *   B,Hq,Hkv,N,d  sizes; Hq must be a multiple of Hkv; query head h reads kv
+ *           head h / (Hq/Hkv) (contiguous groups).  d must be 64 or 128.
+ *           Any N >= 1 is accepted (ragged last tiles are handled in-kernel).
+ *   causal  0: every key visible.  non-zero: key j visible to query i iff j <= i.
+ *   scale   multiplies q.k before the softmax; passed through unchecked.
+ *   dtype   an attn_dtype.  For ATTN_FP8_E4M3 the bytes are taken as the e4m3
+ *           values themselves (all de-scales 1); see attn_fwd_fp8.
+ *   stream  a hipStream_t (NULL = the default stream).
+ *
+ * Returns an attn_status.
+ */
+int attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
+             int B, int Hq, int Hkv, int N, int d, int causal, float scale,
+             int dtype, void* stream);
+
+/*
+ * attn_fwd_fp8 -- the same operation on per-tensor-scaled e4m3 inputs: the real
+ * tensors are q_descale*q, k_descale*k, v_descale*v.  q_descale*k_descale is
+ * folded into the softmax exponent and v_descale into the final normalisation,
+ * so no extra pass over memory is made.  P is re-quantised to e4m3 before the
+ * second product; o is bfloat16, lse float32.
+ */
+int attn_fwd_fp8(const void* q, const void* k, const void* v, void* o, float* lse,
+                 int B, int Hq, int Hkv, int N, int d, int causal, float scale,
+                 float q_descale, float k_descale, float v_descale, void* stream);
+
+/*
+ * attn_fwd_variant -- tuning hook: as attn_fwd, but with the kernel variant
+ * forced (see attn_variant_name) instead of chosen by the library.  Returns
+ * ATTN_ERR_UNSUPPORTED if the variant does not exist for this d / dtype.
+ */
+int attn_fwd_variant(const void* q, const void* k, const void* v, void* o, float* lse,
+                     int B, int Hq, int Hkv, int N, int d, int causal, float scale,
+                     int dtype, int variant, void* stream);
+
+/* Number of kernel variants and a host string describing variant i (NULL if out of range). */
+int attn_num_variants(void);
+const char* attn_variant_name(int variant);
+
+/*
+ * attn_tile_coord -- host-side copy of the work decomposition the kernels use:
+ * workgroup `wg` of a launch of attn_num_workgroups(...) workgroups processes
+ * query tile *t (rows t*BM .. t*BM+BM-1) of head *hq in batch *b.  Host
+ * pointers.  Used to check that the map is a bijection and keeps the
+ * workgroups that share a K/V head on one XCD.  Returns an attn_status.
+ */
+int attn_tile_coord(int wg, int B, int Hq, int Hkv, int N, int BM, int causal,
+                    int* b, int* hq, int* t);
+int attn_num_workgroups(int B, int Hq, int N, int BM);
+
+/* Query-tile height BM (rows per workgroup) of a variant; 0 if out of range. */
+int attn_variant_bm(int variant);
+
+const char* attn_status_string(int status); /* host string, static storage */
+int attn_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ATTN_MI355X_H */

@@ -1,0 +1,154 @@
+// C-ABI entry points: argument validation, variant choice, launch.  See include/attn.h.
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdint.h>
+
+#include "../../include/attn.h"
+#include "attn_kernels.h"
+#include "tile_map.h"
+
+namespace {
+
+constexpr int kVersion = 1;
+constexpr float kLog2e = 1.4426950408889634f;
+
+const AttnVariant* variant_at(int i) {
+  int n = 0;
+  const AttnVariant* t = attn_bf16_variants(&n);
+  if (i < 0 || i >= n) return nullptr;
+  return &t[i];
+}
+int total_variants() {
+  int n = 0;
+  attn_bf16_variants(&n);
+  return n;
+}
+
+bool misaligned(const void* p, uintptr_t a) { return ((uintptr_t)p & (a - 1)) != 0; }
+
+int validate(const void* q, const void* k, const void* v, void* o, float* lse, int B, int Hq, int Hkv, int N, int d,
+             float scale, int dtype) {
+  if (!q || !k || !v || !o || !lse) return ATTN_ERR_NULL;
+  if (dtype != ATTN_BF16 && dtype != ATTN_FP8_E4M3) return ATTN_ERR_DTYPE;
+  if (B <= 0 || Hq <= 0 || Hkv <= 0 || N <= 0 || d <= 0) return ATTN_ERR_SHAPE;
+  if (Hq % Hkv != 0) return ATTN_ERR_SHAPE;
+  if (misaligned(q, 16) || misaligned(k, 16) || misaligned(v, 16) || misaligned(o, 16) || misaligned(lse, 4)) return ATTN_ERR_SHAPE;
+  if (d != 64 && d != 128) return ATTN_ERR_UNSUPPORTED;
+  // the kernels take the row maximum of the raw products and scale it afterwards,
+  // which needs a positive factor; NaN and +inf pass through (garbage in, garbage out)
+  if (scale <= 0.0f) return ATTN_ERR_UNSUPPORTED;
+  // element offsets inside one head are 32-bit in the kernels
+  if ((long long)N * d * 2 >= (1ll << 31)) return ATTN_ERR_UNSUPPORTED;
+  return ATTN_OK;
+}
+
+// Default choice: the widest query tile for long sequences (fewest K/V re-reads per
+// query row), the 128-row tile when the launch would otherwise not fill the chip.
+int choose_variant(int dtype, int B, int Hq, int N, int d) {
+  int best = -1;
+  for (int i = 0; i < total_variants(); ++i) {
+    const AttnVariant* a = variant_at(i);
+    if (a->dtype != dtype || a->d != d) continue;
+    if (best < 0) { best = i; continue; }
+  }
+  if (best < 0) return -1;
+  // first listed variant for (dtype,d) is the default; fall back to a smaller tile if
+  // the grid would leave most of the 256 CUs idle
+  const AttnVariant* a = variant_at(best);
+  long long wgs = (long long)B * Hq * ((N + a->bm - 1) / a->bm);
+  if (wgs < 256) {
+    for (int i = 0; i < total_variants(); ++i) {
+      const AttnVariant* c = variant_at(i);
+      if (c->dtype == dtype && c->d == d && c->bm < a->bm && c->threads <= 256) { best = i; break; }
+    }
+  }
+  return best;
+}
+
+int run(const void* q, const void* k, const void* v, void* o, float* lse, int B, int Hq, int Hkv, int N, int d, int causal,
+        float scale, int dtype, float qk_descale, float v_descale, int variant, void* stream) {
+  int st = validate(q, k, v, o, lse, B, Hq, Hkv, N, d, scale, dtype);
+  if (st != ATTN_OK) return st;
+  if (variant < 0) variant = choose_variant(dtype, B, Hq, N, d);
+  const AttnVariant* a = variant_at(variant);
+  if (!a || a->dtype != dtype || a->d != d) return ATTN_ERR_UNSUPPORTED;
+  AttnParams p;
+  p.q = q; p.k = k; p.v = v; p.o = o; p.lse = lse;
+  p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.N = N;
+  p.T = (N + a->bm - 1) / a->bm;
+  p.causal = causal ? 1 : 0;
+  p.scale_log2 = scale * qk_descale * kLog2e;
+  p.out_scale = v_descale;
+  const long long grid = (long long)B * Hq * p.T;
+  if (grid <= 0 || grid > 0x7fffffffll) return ATTN_ERR_UNSUPPORTED;
+  const int err = a->launch(p, (int)grid, (hipStream_t)stream);
+  return err == 0 ? ATTN_OK : ATTN_ERR_LAUNCH;
+}
+
+}  // namespace
+
+extern "C" {
+
+int attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse, int B, int Hq, int Hkv, int N, int d, int causal,
+             float scale, int dtype, void* stream) {
+  return run(q, k, v, o, lse, B, Hq, Hkv, N, d, causal, scale, dtype, 1.0f, 1.0f, -1, stream);
+}
+
+int attn_fwd_fp8(const void* q, const void* k, const void* v, void* o, float* lse, int B, int Hq, int Hkv, int N, int d, int causal,
+                 float scale, float q_descale, float k_descale, float v_descale, void* stream) {
+  if (!(q_descale > 0.0f) || !(k_descale > 0.0f)) return ATTN_ERR_UNSUPPORTED;
+  return run(q, k, v, o, lse, B, Hq, Hkv, N, d, causal, scale, ATTN_FP8_E4M3, q_descale * k_descale, v_descale, -1, stream);
+}
+
+int attn_fwd_variant(const void* q, const void* k, const void* v, void* o, float* lse, int B, int Hq, int Hkv, int N, int d,
+                     int causal, float scale, int dtype, int variant, void* stream) {
+  if (variant < 0 || variant >= total_variants()) {
+    int st = validate(q, k, v, o, lse, B, Hq, Hkv, N, d, scale, dtype);
+    return st != ATTN_OK ? st : ATTN_ERR_UNSUPPORTED;
+  }
+  return run(q, k, v, o, lse, B, Hq, Hkv, N, d, causal, scale, dtype, 1.0f, 1.0f, variant, stream);
+}
+
+int attn_num_variants(void) { return total_variants(); }
+
+const char* attn_variant_name(int variant) {
+  const AttnVariant* a = variant_at(variant);
+  return a ? a->name : nullptr;
+}
+
+int attn_variant_bm(int variant) {
+  const AttnVariant* a = variant_at(variant);
+  return a ? a->bm : 0;
+}
+
+int attn_num_workgroups(int B, int Hq, int N, int BM) {
+  if (B <= 0 || Hq <= 0 || N <= 0 || BM <= 0) return 0;
+  const long long g = (long long)B * Hq * ((N + BM - 1) / BM);
+  return g > 0x7fffffffll ? 0 : (int)g;
+}
+
+int attn_tile_coord(int wg, int B, int Hq, int Hkv, int N, int BM, int causal, int* b, int* hq, int* t) {
+  if (!b || !hq || !t) return ATTN_ERR_NULL;
+  if (B <= 0 || Hq <= 0 || Hkv <= 0 || N <= 0 || BM <= 0 || Hq % Hkv != 0) return ATTN_ERR_SHAPE;
+  const int T = (N + BM - 1) / BM;
+  if (wg < 0 || (long long)wg >= (long long)B * Hq * T) return ATTN_ERR_SHAPE;
+  const AttnTileCoord c = attn_tile_coord_impl(wg, B, Hq, Hkv, T, causal ? 1 : 0);
+  *b = c.b; *hq = c.hq; *t = c.t;
+  return ATTN_OK;
+}
+
+const char* attn_status_string(int status) {
+  switch (status) {
+    case ATTN_OK: return "ok";
+    case ATTN_ERR_NULL: return "null pointer";
+    case ATTN_ERR_SHAPE: return "bad shape or alignment";
+    case ATTN_ERR_DTYPE: return "unknown dtype";
+    case ATTN_ERR_UNSUPPORTED: return "unsupported configuration";
+    case ATTN_ERR_LAUNCH: return "kernel launch failed";
+    default: return "unknown status";
+  }
+}
+
+int attn_version(void) { return kVersion; }
+
+}  // extern "C"

@@ -1,0 +1,31 @@
+// Internal interface between the C-ABI entry points and the HIP kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+
+struct AttnParams {
+  const void* q;
+  const void* k;
+  const void* v;
+  void* o;
+  float* lse;
+  int B, Hq, Hkv, N;
+  int T;             // query tiles per head = ceil(N / BM)
+  int causal;
+  float scale_log2;  // scale * log2(e) (times q_descale*k_descale for fp8)
+  float out_scale;   // multiplies O in the epilogue (v_descale and P scaling for fp8; 1 for bf16)
+};
+
+struct AttnVariant {
+  const char* name;
+  int dtype;   // attn_dtype
+  int d;       // head dim
+  int bm;      // query rows per workgroup
+  int bn;      // keys per streamed K/V tile
+  int threads; // workgroup size
+  int lds;     // dynamic LDS bytes
+  // launches the kernel for `grid` workgroups on `stream`; returns the hipError_t as int
+  int (*launch)(const AttnParams& p, int grid, hipStream_t stream);
+};
+
+// Variant tables, defined by the kernel translation units (host functions).
+const AttnVariant* attn_bf16_variants(int* count);

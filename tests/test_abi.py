@@ -1,0 +1,108 @@
+"""CPU-side checks of the boundary: the library loads, exports every symbol the
+header declares, rejects bad arguments before touching a device, and its work
+decomposition is a bijection that keeps K/V sharers on one XCD."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def A():
+    import paper_2605_10905_amd as A
+
+    return A
+
+
+def header_functions():
+    text = open(os.path.join(ROOT, "include", "attn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(attn_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(A):
+    names = header_functions()
+    assert "attn_fwd" in names and "attn_fwd_fp8" in names and len(names) >= 9
+    for n in names:
+        assert hasattr(A.lib, n), f"{n} declared in include/attn.h but not exported"
+
+
+def test_header_compiles_as_c():
+    import subprocess
+    import tempfile
+
+    with tempfile.TemporaryDirectory() as td:
+        src = os.path.join(td, "t.c")
+        open(src, "w").write('#include "attn.h"\nint main(void){return attn_version() == 0;}\n')
+        subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"), "-c", src,
+                        "-o", os.path.join(td, "t.o")], check=True)
+
+
+def test_status_strings_and_version(A):
+    assert A.attn_version() >= 1
+    assert A.attn_status_string(0) == "ok"
+    assert len({A.attn_status_string(i) for i in range(6)}) == 6
+    assert A.attn_num_variants() >= 1
+    assert A.attn_variant_name(-1) is None and A.attn_variant_name(10 ** 6) is None
+    assert all(A.attn_variant_bm(i) % 32 == 0 for i in range(A.attn_num_variants()))
+
+
+def test_argument_validation_without_a_device(A):
+    # (fake, never dereferenced) aligned addresses; every call must fail before any launch
+    p = 0x1000
+    ok = dict(B=1, Hq=2, Hkv=1, N=8, d=64)
+
+    def call(q=p, k=p, v=p, o=p, lse=p, causal=0, scale=0.5, dtype=0, **kw):
+        a = dict(ok, **kw)
+        return A.attn_fwd(q, k, v, o, lse, a["B"], a["Hq"], a["Hkv"], a["N"], a["d"], causal, scale, dtype, stream=0,
+                          check=False)
+
+    assert call(q=None) == 1 and call(lse=None) == 1 and call(o=None) == 1
+    assert call(B=0) == 2 and call(N=-1) == 2 and call(Hq=3, Hkv=2) == 2
+    assert call(q=p + 8) == 2 and call(lse=p + 2) == 2
+    assert call(dtype=7) == 3
+    assert call(d=96) == 4 and call(d=256) == 4
+    assert call(scale=0.0) == 4 and call(scale=-1.0) == 4
+    with pytest.raises(A.AttnError):
+        A.attn_fwd(None, p, p, p, p, 1, 1, 1, 8, 64, 0, 1.0, 0, stream=0)
+    assert A.attn_fwd_variant(p, p, p, p, p, 1, 1, 1, 8, 64, 0, 1.0, 0, 10 ** 6, stream=0, check=False) == 4
+    assert A.attn_fwd_fp8(p, p, p, p, p, 1, 1, 1, 8, 64, 0, 1.0, -1.0, 1.0, 1.0, stream=0, check=False) == 4
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,N,BM,causal", [
+    (2, 32, 32, 8192, 256, 0), (4, 64, 8, 4096, 256, 1), (4, 16, 16, 2048, 256, 1), (1, 2, 2, 256, 128, 0),
+    (3, 6, 2, 1000, 128, 1), (1, 1, 1, 1, 256, 0),
+])
+def test_tile_map_is_a_bijection_and_xcd_local(A, B, Hq, Hkv, N, BM, causal):
+    n = A.attn_num_workgroups(B, Hq, N, BM)
+    T = (N + BM - 1) // BM
+    assert n == B * Hq * T
+    seen = set()
+    xcd_of_kv = {}
+    G = Hq // Hkv
+    first_t_of_head = {}
+    for wg in range(n):
+        b, h, t = A.attn_tile_coord(wg, B, Hq, Hkv, N, BM, causal)
+        assert 0 <= b < B and 0 <= h < Hq and 0 <= t < T
+        seen.add((b, h, t))
+        if (B * Hkv) % 8 == 0:
+            xcd_of_kv.setdefault((b, h // G), set()).add(wg % 8)
+        first_t_of_head.setdefault((b, h), t)
+    assert len(seen) == n
+    for s in xcd_of_kv.values():
+        assert len(s) == 1  # all workgroups that share a K/V head run on one XCD
+    if causal:
+        assert all(t == T - 1 for t in first_t_of_head.values())  # heaviest tile first
+    with pytest.raises(A.AttnError):
+        A.attn_tile_coord(n, B, Hq, Hkv, N, BM, causal)
+
+
+def test_no_product_code_imports_the_oracle():
+    for dirpath, _, files in os.walk(os.path.join(ROOT, "paper_2605_10905_amd")):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "from oracle" not in text and "import oracle" not in text

@@ -1,0 +1,157 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on
+the same seeded inputs.  Tolerances are the stated ones (bf16: max-abs 2e-2,
+relative Frobenius 5e-3, lse 1e-3 absolute)."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from tests import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+
+def _variants(d, dtype=0):
+    import paper_2605_10905_amd as A
+
+    return [i for i in range(A.attn_num_variants())
+            if f" d{d} " in A.attn_variant_name(i) and A.attn_variant_name(i).startswith("bf16" if dtype == 0 else "fp8")]
+
+
+def test_library_is_native_and_loaded():
+    import paper_2605_10905_amd as A
+
+    assert A.lib_path.endswith("libattn_mi355x.so") and A.attn_version() >= 1
+
+
+def test_config1_tiny_all_variants():
+    cfg = wl.CONFIGS[0]
+    inp = wl.make_inputs(cfg)
+    dev = gu.to_device(inp)
+    for var in [None] + _variants(64):
+        print("config1 variant", var, flush=True)
+        o, lse = gu.run_gpu(inp, dev, var)
+        gu.check_full(inp, o, lse, f"config1 variant {var}")
+
+
+# reduced-size versions of the graded configs: several tiles, ragged tails, both masks, GQA
+SMALL = [
+    # (config index, B, Hq, Hkv, N)
+    (1, 1, 2, 2, 2048),
+    (1, 2, 2, 2, 1000),
+    (1, 1, 2, 2, 257),
+    (2, 1, 2, 2, 2048),
+    (2, 1, 2, 2, 1531),
+    (3, 1, 8, 2, 1024),
+    (3, 2, 8, 1, 777),
+    (0, 1, 2, 2, 1000),
+    (0, 1, 4, 2, 333),
+]
+
+
+@pytest.mark.parametrize("ci,B,Hq,Hkv,N", SMALL)
+def test_reduced_configs_all_variants(ci, B, Hq, Hkv, N):
+    cfg = wl.CONFIGS[ci]
+    inp = wl.make_inputs(cfg, B=B, Hq=Hq, Hkv=Hkv, N=N)
+    dev = gu.to_device(inp)
+    for var in [None] + _variants(cfg["d"]):
+        print(f"config{ci + 1} reduced B={B} Hq={Hq} Hkv={Hkv} N={N} variant {var}", flush=True)
+        o, lse = gu.run_gpu(inp, dev, var)
+        gu.check_full(inp, o, lse, f"cfg{ci + 1} N={N} variant {var}")
+
+
+@pytest.mark.parametrize("N", [1, 2, 31, 32, 33, 63, 64, 65, 127, 129, 255, 256, 511, 513])
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("d", [64, 128])
+def test_edge_lengths(N, causal, d):
+    cfg = dict(wl.CONFIGS[0], d=d, causal=causal, scale=1.0 / d ** 0.5, seed=77 + N)
+    inp = wl.make_inputs(cfg, B=1, Hq=2, Hkv=1, N=N)
+    dev = gu.to_device(inp)
+    for var in [None] + _variants(d):
+        print(f"edge N={N} causal={causal} d={d} variant {var}", flush=True)
+        o, lse = gu.run_gpu(inp, dev, var)
+        gu.check_full(inp, o, lse, f"edge N={N} causal={causal} d={d} variant {var}")
+
+
+def _bits(x):
+    return wl.f32_to_bf16_bits(np.asarray(x, dtype=np.float32))
+
+
+def _custom(q, k, v, causal, scale):
+    B, Hq, N, d = q.shape
+    return dict(B=B, Hq=Hq, Hkv=k.shape[1], N=N, d=d, causal=causal, scale=scale, dtype="bf16",
+                q=_bits(q), k=_bits(k), v=_bits(v), descale=(1.0, 1.0, 1.0))
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_adversarial_rows(causal):
+    """Degenerate score patterns: a late dominant key (large rescale), all-equal
+    scores, a monotonically growing maximum, large magnitudes."""
+    rng = np.random.default_rng(5)
+    N, d = 640, 128
+    scale = 1.0 / d ** 0.5
+    v = rng.standard_normal((1, 1, N, d)).astype(np.float32)
+    cases = {}
+    q = rng.standard_normal((1, 1, N, d)).astype(np.float32)
+    k = rng.standard_normal((1, 1, N, d)).astype(np.float32)
+    k2 = k.copy(); k2[0, 0, 600] = 6.0 * q[0, 0, 620] / np.linalg.norm(q[0, 0, 620]) * 4
+    cases["late_dominant_key"] = (q, k2)
+    cases["all_equal_scores"] = (q, np.zeros_like(k))
+    ramp = np.zeros_like(k); ramp[0, 0, :, 0] = np.arange(N) * 0.25
+    q3 = np.abs(q); q3[..., 0] = 4.0
+    cases["growing_max"] = (q3, ramp)
+    cases["large_magnitude"] = (q * 6, k * 6)
+    for name, (qq, kk) in cases.items():
+        inp = _custom(qq, kk, v, causal, scale)
+        dev = gu.to_device(inp)
+        for var in [None] + _variants(d):
+            print(f"adversarial {name} causal={causal} variant {var}", flush=True)
+            o, lse = gu.run_gpu(inp, dev, var)
+            gu.check_full(inp, o, lse, f"{name} causal={causal} variant {var}")
+
+
+def test_run_to_run_determinism():
+    cfg = wl.CONFIGS[1]
+    inp = wl.make_inputs(cfg, B=1, Hq=4, Hkv=4, N=2048)
+    dev = gu.to_device(inp)
+    o1, l1 = gu.run_gpu(inp, dev)
+    o2, l2 = gu.run_gpu(inp, dev)
+    assert torch.equal(o1.view(torch.int16), o2.view(torch.int16)) and torch.equal(l1, l2)
+
+
+# ---- full-size graded configs, in the launch configuration bench.py times ------------
+@pytest.mark.parametrize("ci", [1, 2, 3])
+def test_full_size_sampled(ci):
+    import paper_2605_10905_amd as A
+
+    cfg = wl.CONFIGS[ci]
+    print(f"full-size config{ci + 1}: generating inputs", flush=True)
+    inp = wl.make_inputs(cfg)
+    dev = gu.to_device(inp)
+    print(f"full-size config{ci + 1}: launching", flush=True)
+    o, lse = gu.run_gpu(inp, dev)
+    assert torch.isfinite(o.float()).all() and torch.isfinite(lse).all()
+    rng = np.random.default_rng(100 + ci)
+    B, Hq, N = cfg["B"], cfg["Hq"], cfg["N"]
+    heads = [(0, 0), (B - 1, Hq - 1), (int(rng.integers(0, B)), int(rng.integers(0, Hq))),
+             (int(rng.integers(0, B)), int(rng.integers(0, Hq)))]
+    rows = [gu.sample_rows(N, 256, rng) for _ in heads]
+    print(f"full-size config{ci + 1}: oracle on {sum(len(r) for r in rows)} sampled rows", flush=True)
+    m = gu.check_sampled(inp, o, lse, heads, rows, f"config{ci + 1} full size")
+    print(f"full-size config{ci + 1}: {m}", flush=True)
+    # properties that hold at any size: lse bounds from the row maximum of the scores
+    # (max <= lse <= max + ln(#visible keys)) checked on one whole head via O(N d) work
+    # is not available without the scores; instead check O rows are convex combinations
+    # of V rows: every output coordinate lies within the min/max of its V column.
+    b, h = heads[1]
+    g = h // (Hq // cfg["Hkv"])
+    vcol = dev["v"][b, g].float()
+    oo = o[b, h].float()
+    if cfg["causal"]:
+        hi = torch.cummax(vcol, dim=0).values
+        lo = torch.cummin(vcol, dim=0).values
+    else:
+        hi = vcol.max(dim=0, keepdim=True).values
+        lo = vcol.min(dim=0, keepdim=True).values
+    eps = 1e-2 * (hi - lo).abs() + 1e-6
+    assert bool(((oo <= hi + eps) & (oo >= lo - eps)).all())
