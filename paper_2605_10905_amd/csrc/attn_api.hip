@@ -12,16 +12,22 @@ namespace {
 constexpr int kVersion = 1;
 constexpr float kLog2e = 1.4426950408889634f;
 
+// all variant tables, concatenated; the first match for (dtype, d) is the default
 const AttnVariant* variant_at(int i) {
+  if (i < 0) return nullptr;
   int n = 0;
-  const AttnVariant* t = attn_bf16_variants(&n);
-  if (i < 0 || i >= n) return nullptr;
-  return &t[i];
+  const AttnVariant* t = attn_bf16_pp_variants(&n);
+  if (i < n) return &t[i];
+  i -= n;
+  t = attn_bf16_variants(&n);
+  if (i < n) return &t[i];
+  return nullptr;
 }
 int total_variants() {
-  int n = 0;
-  attn_bf16_variants(&n);
-  return n;
+  int a = 0, b = 0;
+  attn_bf16_pp_variants(&a);
+  attn_bf16_variants(&b);
+  return a + b;
 }
 
 bool misaligned(const void* p, uintptr_t a) { return ((uintptr_t)p & (a - 1)) != 0; }
