@@ -85,6 +85,14 @@ __device__ __forceinline__ void wg_barrier() {
   __builtin_amdgcn_sched_barrier(0);
 }
 
+#ifdef ATTN_PHASE_TIMING
+__device__ long long g_phase_timing[8][4];
+#define PT_NOW() __builtin_readcyclecounter()
+#define PT_ADD(slot, t0) do { const long long t1_ = PT_NOW(); pt[slot] += t1_ - (t0); (t0) = t1_; } while (0)
+#else
+#define PT_ADD(slot, t0) do { } while (0)
+#endif
+
 constexpr float kTau = 8.0f;  // the running max may lag a block max by up to 2^8 before a rescale
 
 template <int D, bool CAUSAL>
@@ -228,6 +236,11 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_bf16_pp_kernel(const AttnPara
 
   // VALU phase: mask, row max, (rare) rescale, P = exp2(c S - m_ref), row sum
   auto valu_phase = [&](int key0, bool need_mask) __attribute__((always_inline)) {
+#ifdef ATTN_EXP_SKIP_VALU
+    pk[0] = u32x4{0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u}; pk[1] = pk[0]; l_run += 1.f; m_ref = 0.f;
+    asm volatile("" : "+v"(pk[0]), "+v"(pk[1]), "+v"(l_run));
+    return;
+#endif
     if (need_mask) {
       const int kbase = key0 + 4 * h;
 #pragma unroll
@@ -269,6 +282,9 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_bf16_pp_kernel(const AttnPara
   // the next block is one this wave never consumes, its S^T is computed on whatever the
   // LDS slot holds and then ignored.
   auto mfma_phase = [&](auto voff, auto koff) __attribute__((always_inline)) {
+#ifdef ATTN_EXP_SKIP_MFMA
+    return;
+#endif
 #pragma unroll
     for (int r = 0; r < 16; ++r) s[r] = 0.f;
     constexpr int NPV = NCB * 2;
@@ -279,6 +295,47 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_bf16_pp_kernel(const AttnPara
         s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[i], s, 0, 0, 0);
       }
       if (i < NPV) pv_step(voff, i % NCB, i / NCB);
+    }
+  };
+
+  // Operands of the first half of an MFMA phase, read from LDS at the END of the preceding
+  // VALU phase (before the phase barrier), so that the matrix pipe starts the moment the
+  // barrier opens instead of waiting for LDS latency.
+  constexpr int KP = NKK / 2;  // K operands read ahead (k-steps 0 .. KP-1)
+  bf16x8 kpre[KP];
+  s16x8 vpre[NCB];             // V operands of the first 16 keys, all column blocks
+  auto v_operand = [&](auto voff, int cb, int kc) __attribute__((always_inline)) {
+    const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(smem + vaddr[cb][0] + voff + kc * 16 * ROWB));
+    const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(smem + vaddr[cb][1] + voff + kc * 16 * ROWB));
+    s16x8 av;
+    av[0] = v0[0]; av[1] = v0[1]; av[2] = v0[2]; av[3] = v0[3];
+    av[4] = v1[0]; av[5] = v1[1]; av[6] = v1[2]; av[7] = v1[3];
+    return av;
+  };
+  auto read_ahead = [&](auto voff, auto koff) __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < (KP > NCB ? KP : NCB); ++i) {
+      if (i < KP) kpre[i] = *(LDS_AS bf16x8*)(smem + kaddr[i] + koff);
+      if (i < NCB) vpre[i] = v_operand(voff, i, 0);
+    }
+  };
+  // The phase itself, in a fixed order: step i issues the i-th QK^T MFMA and the i-th PV MFMA
+  // (independent accumulators, so neither waits for the other), then requests the operands of
+  // step i + KP into the registers it has just freed.
+  auto mfma_phase_ra = [&](auto voff, auto koff) __attribute__((always_inline)) {
+    static_assert(NKK == 2 * NCB && KP == NCB, "step pairing assumes D/16 QK steps and 2*D/32 PV steps");
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s[r] = 0.f;
+#pragma unroll
+    for (int i = 0; i < NKK; ++i) {
+      const int cb = i % NCB, kc = i / NCB;
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kpre[i % KP], qf[i], s, 0, 0, 0);
+      oacc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vpre[cb]), __builtin_bit_cast(bf16x8, pk[kc]), oacc[cb], 0, 0, 0);
+      if (i < KP) {
+        kpre[i] = *(LDS_AS bf16x8*)(smem + kaddr[i + KP] + koff);
+        vpre[cb] = v_operand(voff, cb, 1);
+      }
+      __builtin_amdgcn_sched_barrier(0);
     }
   };
 
@@ -295,32 +352,54 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_bf16_pp_kernel(const AttnPara
   auto is_active = [&](int key0) __attribute__((always_inline)) {
     return wave_valid && key0 < kv_end && (!CAUSAL || key0 <= wlast);
   };
-  // producer step at the start of the first MFMA phase of tile j, and the matching wait at
-  // its end: tile j+1 is published by the coming barrier, tile j+2 may stay in flight
+  // producer step: tile j+2 is requested at the start of the first MFMA phase of tile j and
+  // waited for at the end of the first VALU phase of tile j+1, so that the barrier closing
+  // that phase publishes it
   auto prefetch = [&](int j, int slot) __attribute__((always_inline)) {
     if (j + 2 < nt) issue_tile_loads(j + 2, slot);
   };
-  auto publish_wait = [&](int j) __attribute__((always_inline)) {
-    if (j + 2 < nt) WAIT_VMCNT(2 * NLD);
-    else WAIT_VMCNT(0);
-  };
+  // tile j+1 was requested four phases ago; its loads are the only ones in flight here
+  auto publish_wait = [&]() __attribute__((always_inline)) { WAIT_VMCNT(0); };
 
   // A tile whose 64 keys are visible to every query of the wave: straight-line code, all
   // LDS offsets are immediates (SLOT is a compile-time constant).
+#ifdef ATTN_PHASE_TIMING
+  long long pt[4] = {0, 0, 0, 0};
+  long long tp = PT_NOW();
+#else
+  int tp = 0;
+#endif
   auto tile_hot = [&](int j, auto slot_tag) __attribute__((always_inline)) {
     constexpr int SLOT = decltype(slot_tag)::value;
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
-      valu_phase(0, false);
-      wg_barrier();
-      if (kb == 0) prefetch(j, (SLOT + 2) % NSLOT);
-      __builtin_amdgcn_s_setprio(1);
-      if (kb == 0) mfma_phase(std::integral_constant<int, SLOT * TILEB>{}, std::integral_constant<int, SLOT * TILEB + SUBB>{});
-      else mfma_phase(std::integral_constant<int, SLOT * TILEB + SUBB>{}, std::integral_constant<int, ((SLOT + 1) % NSLOT) * TILEB>{});
-      __builtin_amdgcn_s_setprio(0);
-      if (kb == 0) publish_wait(j);
-      wg_barrier();
-    }
+    constexpr std::integral_constant<int, SLOT * TILEB> v0off{};
+    constexpr std::integral_constant<int, SLOT * TILEB + SUBB> v1off{}, k1off{};
+    constexpr std::integral_constant<int, ((SLOT + 1) % NSLOT) * TILEB> knoff{};
+    // first 32 keys
+    valu_phase(0, false);
+    read_ahead(v0off, k1off);
+    publish_wait();
+    PT_ADD(0, tp);
+    wg_barrier();
+    PT_ADD(1, tp);
+    prefetch(j, (SLOT + 2) % NSLOT);
+    __builtin_amdgcn_s_setprio(1);
+    mfma_phase_ra(v0off, k1off);
+    __builtin_amdgcn_s_setprio(0);
+    PT_ADD(2, tp);
+    wg_barrier();
+    PT_ADD(3, tp);
+    // second 32 keys; the S^T computed here belongs to the first block of tile j+1
+    valu_phase(0, false);
+    read_ahead(v1off, knoff);
+    PT_ADD(0, tp);
+    wg_barrier();
+    PT_ADD(1, tp);
+    __builtin_amdgcn_s_setprio(1);
+    mfma_phase_ra(v1off, knoff);
+    __builtin_amdgcn_s_setprio(0);
+    PT_ADD(2, tp);
+    wg_barrier();
+    PT_ADD(3, tp);
   };
   // Any tile: blocks may be partly masked (causal diagonal, ragged end of K) or not visible
   // to this wave at all; the ring slot is a run-time value.
@@ -331,6 +410,7 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_bf16_pp_kernel(const AttnPara
       const int key0 = j * BN + kb * 32;
       const bool active = is_active(key0);
       if (active) valu_phase(key0, (CAUSAL && key0 + 31 > wq0) || key0 + 31 >= N);
+      if (kb == 0) publish_wait();
       wg_barrier();
       if (kb == 0) prefetch(j, slot >= 1 ? slot - 1 : NSLOT - 1);
       if (active) {
@@ -339,7 +419,6 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_bf16_pp_kernel(const AttnPara
         else mfma_phase(slot * TILEB + SUBB, nslot * TILEB);
         __builtin_amdgcn_s_setprio(0);
       }
-      if (kb == 0) publish_wait(j);
       wg_barrier();
     }
   };
@@ -358,6 +437,10 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_bf16_pp_kernel(const AttnPara
     slot = slot == NSLOT - 1 ? 0 : slot + 1;
   }
   if (grp == 0) wg_barrier();  // balance group 1's extra leading barrier
+#ifdef ATTN_PHASE_TIMING
+  if (blockIdx.x == 0 && lane == 0)
+    for (int i = 0; i < 4; ++i) g_phase_timing[w][i] = pt[i];
+#endif
 
   // ---- epilogue: O = acc / l (bf16), lse = (m + log2 l) * ln 2 ---------------------------
   char* const ohead = (char*)p.o + ((size_t)(tc.b * p.Hq + tc.hq) * N) * ROWB;
@@ -398,6 +481,12 @@ int launch_pp(const AttnParams& p, int grid, hipStream_t stream) {
 }
 
 }  // namespace
+
+#ifdef ATTN_PHASE_TIMING
+extern "C" int attn_debug_phase_timing(long long* out) {
+  return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_phase_timing), sizeof(long long) * 32);
+}
+#endif
 
 const AttnVariant* attn_bf16_pp_variants(int* count) {
   static const AttnVariant table[] = {
