@@ -13,21 +13,27 @@ constexpr int kVersion = 1;
 constexpr float kLog2e = 1.4426950408889634f;
 
 // all variant tables, concatenated; the first match for (dtype, d) is the default
+typedef const AttnVariant* (*VariantTable)(int*);
+const VariantTable kTables[] = {attn_bf16_pp_variants, attn_bf16_sp_variants, attn_bf16_variants};
+
 const AttnVariant* variant_at(int i) {
   if (i < 0) return nullptr;
-  int n = 0;
-  const AttnVariant* t = attn_bf16_pp_variants(&n);
-  if (i < n) return &t[i];
-  i -= n;
-  t = attn_bf16_variants(&n);
-  if (i < n) return &t[i];
+  for (VariantTable tab : kTables) {
+    int n = 0;
+    const AttnVariant* t = tab(&n);
+    if (i < n) return &t[i];
+    i -= n;
+  }
   return nullptr;
 }
 int total_variants() {
-  int a = 0, b = 0;
-  attn_bf16_pp_variants(&a);
-  attn_bf16_variants(&b);
-  return a + b;
+  int total = 0;
+  for (VariantTable tab : kTables) {
+    int n = 0;
+    tab(&n);
+    total += n;
+  }
+  return total;
 }
 
 bool misaligned(const void* p, uintptr_t a) { return ((uintptr_t)p & (a - 1)) != 0; }

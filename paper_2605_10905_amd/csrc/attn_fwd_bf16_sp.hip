@@ -1,0 +1,482 @@
+// Fused attention forward, bf16, gfx950: the software-pipelined kernel.
+//
+// Mathematics and register layout are those of attn_fwd_bf16.hip (transposed products on
+// 32x32x16 bf16 MFMA, one query per lane): paper section 6.1 for the phases, appendix C.3
+// for the streaming-softmax state and the overlap of one block's QK^T product with the
+// previous block's PV product.
+//
+// Orchestration.  All 8 waves of a workgroup run the same instruction stream, and that
+// stream is pipelined over 32-key blocks so that the matrix pipe and the vector pipe are fed
+// from the SAME wave at the same time (measured on gfx950: a wave that issues only MFMAs and
+// a second wave that issues only VALU work overlap poorly, because the vector wave gets an
+// issue slot only every ~9 cycles; one MFMA followed by four to five independent VALU
+// instructions from the same wave is nearly free).  In the step that handles block u a wave
+//     * exponentiates block u            (VALU:  P(u)   = exp2(c S(u) - m))
+//     * computes the scores of block u+1 (MFMA:  S(u+1) = K(u+1) Q^T)
+//     * accumulates block u-1            (MFMA:  O^T   += V(u-1)^T P(u-1)^T)
+// and the three instruction streams are interleaved by hand (program order pinned with
+// scheduling barriers): every MFMA is followed by its share of the exponentials and by the
+// LDS reads of the operands three MFMAs ahead.
+//
+// K/V streaming.  Block u+1 of K and block u-1 of V travel together: "bundle" b holds key
+// tile b+1 and value tile b (64 keys each) and is consumed by exactly one loop iteration, so
+// a three-slot LDS ring with direct-to-LDS loads issued two bundles ahead needs one
+// workgroup barrier per 64 keys: it is both the "full" signal of bundle b+1 and the "empty"
+// signal of bundle b-1 (stage = b mod 3).  The barrier sits between the two 32-key steps of an
+// iteration so that the first K operands of the next iteration can be read one step early.
+//
+// The running maximum is raised only when a block maximum exceeds it by more than 2^8
+// (exact: any reference value is valid as long as nothing overflows), so the accumulator
+// rescale runs once or twice per row; when it does, the already-packed probabilities of the
+// block still waiting for its PV product are rescaled with it.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <type_traits>
+
+#include "attn_device.h"
+#include "attn_kernels.h"
+#include "tile_map.h"
+
+namespace {
+
+constexpr float kTau = 8.0f;
+
+template <int V>
+using ic = std::integral_constant<int, V>;
+
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+  bf16x2 t;
+  t[0] = (__bf16)a;
+  t[1] = (__bf16)b;
+  return __builtin_bit_cast(uint32_t, t);
+}
+
+// max without the NaN-canonicalising self-max the compiler adds around fmaxf of MFMA results
+__device__ __forceinline__ float vmax3(float a, float b, float c) {
+  float d;
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "v"(b), "v"(c));
+  return d;
+}
+__device__ __forceinline__ float vmax2(float a, float b) {
+  float d;
+  asm("v_max_f32 %0, %1, %2" : "=v"(d) : "v"(a), "v"(b));
+  return d;
+}
+__device__ __forceinline__ float vmax_halves(float x) {
+  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return vmax2(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
+template <int D, bool CAUSAL>
+__global__ void __launch_bounds__(512, 2) attn_fwd_bf16_sp_kernel(const AttnParams p) {
+  constexpr int BN = 64, NWAVES = 8, BM = NWAVES * 32, NT = NWAVES * 64;
+  constexpr int NKK = D / 16;       // MFMA k-steps of S^T = K Q^T
+  constexpr int NCB = D / 32;       // 32-row blocks of O^T
+  constexpr int ROWB = D * 2;       // bytes per K/V row
+  constexpr int NCH = ROWB / 16;    // 16-byte chunks per row
+  constexpr int TILEB = BN * ROWB;  // bytes per K (or V) tile
+  constexpr int SUBB = 32 * ROWB;   // bytes per 32-key block
+  constexpr int NSLOT = 3;
+  constexpr int VBASE = NSLOT * TILEB;  // K parts of the slots first, then the V parts
+  constexpr int NLD = BN * NCH / NT;    // direct-to-LDS loads per thread per tile
+  constexpr int NQA = NKK / 2;          // QK^T steps issued before the rescale check
+  constexpr int NOPS = 3 * (NKK - NQA); // MFMAs after it: one QK^T step, then two PV steps, repeated
+#ifndef ATTN_RA
+#define ATTN_RA 5
+#endif
+  constexpr int RA = ATTN_RA;           // operands are read from LDS this many MFMAs ahead
+  static_assert(BN * NCH % NT == 0 && NLD >= 1, "tile must divide evenly over the workgroup");
+  static_assert(2 * NCB == 2 * (NKK - NQA), "two PV steps per late QK^T step");
+  static_assert(NSLOT * TILEB < 65536, "ring offsets must fit the 16-bit LDS immediate");
+
+  __shared__ __attribute__((aligned(1024))) char smem_raw[2 * NSLOT * TILEB];
+  LDS_AS char* const smem = (LDS_AS char*)smem_raw;
+
+  const int tid = threadIdx.x;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+  const int qi = lane & 31;  // query column within the wave's 32-query block
+  const int h = lane >> 5;   // which half of the k-slots / accumulator rows this lane holds
+
+  const AttnTileCoord tc = attn_tile_coord_impl(blockIdx.x, p.B, p.Hq, p.Hkv, p.T, CAUSAL ? 1 : 0);
+  const int N = p.N;
+  const int G = p.Hq / p.Hkv;
+  const int hk = tc.hq / G;
+  const int q0 = tc.t * BM;
+  const int wq0 = q0 + w * 32;  // first query row of this wave
+  const bool wave_valid = wq0 < N;
+
+  const char* const qhead = (const char*)p.q + ((size_t)(tc.b * p.Hq + tc.hq) * N) * ROWB;
+  const char* const khead = (const char*)p.k + ((size_t)(tc.b * p.Hkv + hk) * N) * ROWB;
+  const char* const vhead = (const char*)p.v + ((size_t)(tc.b * p.Hkv + hk) * N) * ROWB;
+
+  const int kv_end = CAUSAL ? min(N, q0 + BM) : N;  // keys the workgroup visits
+  const int nt = (kv_end + BN - 1) / BN;            // 64-key tiles = bundles
+
+  // ---- producer role: direct-to-LDS tile loads ---------------------------------------------
+  int ld_row[NLD];
+  uint32_t ld_koff[NLD], ld_voff[NLD];
+#pragma unroll
+  for (int it = 0; it < NLD; ++it) {
+    const int s = it * NT + tid;
+    const int r = s / NCH, c = s % NCH;
+    ld_row[it] = r;
+    ld_koff[it] = r * ROWB + ((c ^ attn_swz_k<ROWB>(r)) << 4);
+    ld_voff[it] = r * ROWB + ((c ^ attn_swz_v<ROWB>(r)) << 4);
+  }
+  auto issue_tile = [&](const char* head, int t, const uint32_t (&off)[NLD], uint32_t dst) __attribute__((always_inline)) {
+#ifdef ATTN_EXP_SKIP_DMA
+    if (t > 2) return;
+#endif
+    const char* const base = head + (size_t)t * TILEB;
+    if ((t + 1) * BN <= N) {
+#pragma unroll
+      for (int it = 0; it < NLD; ++it) attn_lds_dma16(base, off[it], dst + it * NT * 16);
+    } else {
+      // ragged last tile: rows past N-1 re-read row N-1 (finite data; masked out later)
+#pragma unroll
+      for (int it = 0; it < NLD; ++it) {
+        const uint32_t over = (uint32_t)max(0, t * BN + ld_row[it] - (N - 1)) * ROWB;
+        attn_lds_dma16(base, off[it] - over, dst + it * NT * 16);
+      }
+    }
+  };
+  const uint32_t lds_wave = (uint32_t)(uintptr_t)smem + w * 1024;
+  // bundle b = key tile b+1 (the last tile again if there is none) and value tile b
+  auto issue_bundle = [&](int b, int slot) __attribute__((always_inline)) {
+    issue_tile(khead, min(b + 1, nt - 1), ld_koff, lds_wave + slot * TILEB);
+    issue_tile(vhead, b, ld_voff, lds_wave + VBASE + slot * TILEB);
+  };
+
+  issue_tile(khead, 0, ld_koff, lds_wave + 2 * TILEB);  // key tile 0 borrows the K part of slot 2
+  issue_bundle(0, 0);
+
+  // ---- Q operand (B operand of S^T = K Q^T): lane (qi,h) holds Q[row][16kk+8h .. +7] ----------
+  bf16x8 qf[NKK];
+  {
+    const int row = min(wq0 + qi, N - 1);
+    const char* src = qhead + (size_t)row * ROWB + h * 16;
+#pragma unroll
+    for (int kk = 0; kk < NKK; ++kk) qf[kk] = *(const bf16x8*)(src + kk * 32);
+  }
+  if (nt > 1) issue_bundle(1, 1);
+
+  // ---- LDS read addresses (slot 0, first 32-key block) -----------------------------------------
+  uint32_t kaddr[NKK];
+#pragma unroll
+  for (int kk = 0; kk < NKK; ++kk) kaddr[kk] = qi * ROWB + (((2 * kk + h) ^ attn_swz_k<ROWB>(qi)) << 4);
+  // V through the transposing load: in a group of 16 lanes, lane s reads the four columns
+  // 4*(s%4).. of key row s/4 and the hardware hands lane t the four keys of column t.
+  uint32_t vaddr[NCB][2];
+  {
+    const int s = lane & 15, chalf = (lane >> 4) & 1;
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+      for (int e = 0; e < 2; ++e) {
+        const int key = 8 * e + 4 * h + (s >> 2);
+        const int chunk = cb * 4 + chalf * 2 + ((s & 3) >> 1);
+        vaddr[cb][e] = VBASE + key * ROWB + ((chunk ^ attn_swz_v<ROWB>(key)) << 4) + ((s & 1) << 3);
+      }
+  }
+  auto k_operand = [&](auto koff, int kk) __attribute__((always_inline)) {
+#if defined(ATTN_EXP_SKIP_LDS) || defined(ATTN_EXP_SKIP_LDSK)
+    return u32x4{kaddr[kk], kaddr[kk], 0x3f803f80u, 0x3f803f80u};
+#endif
+    return __builtin_bit_cast(u32x4, *(LDS_AS bf16x8*)(smem + kaddr[kk] + koff));
+  };
+  auto v_operand = [&](auto voff, int cb, int kc) __attribute__((always_inline)) {
+#if defined(ATTN_EXP_SKIP_LDS) || defined(ATTN_EXP_SKIP_LDSV)
+    return u32x4{vaddr[cb][0], vaddr[cb][1], 0x3f803f80u, 0x3f803f80u};
+#endif
+    const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(smem + vaddr[cb][0] + voff + kc * 16 * ROWB));
+    const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(smem + vaddr[cb][1] + voff + kc * 16 * ROWB));
+    s16x8 av;
+    av[0] = v0[0]; av[1] = v0[1]; av[2] = v0[2]; av[3] = v0[3];
+    av[4] = v1[0]; av[5] = v1[1]; av[6] = v1[2]; av[7] = v1[3];
+    return __builtin_bit_cast(u32x4, av);
+  };
+
+  // ---- streaming-softmax state ----------------------------------------------------------------
+  f32x16 oacc[NCB];
+#pragma unroll
+  for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) oacc[cb][r] = 0.f;
+  float m_ref = -INFINITY;  // reference maximum, scaled log2 units
+  float l_run = 0.f;        // this lane's share of the row sum (halves are added at the end)
+  const float c = p.scale_log2;
+  const int qrow = wq0 + qi;
+  const int limit = CAUSAL ? min(qrow, N - 1) : (N - 1);  // last visible key of this lane's query
+  const int wlast = wq0 + 31;
+
+  f32x16 s_a, s_b;        // S^T of two consecutive blocks (one consumed, one produced)
+  u32x4 p_a[2], p_b[2];   // packed P^T of two consecutive blocks (one produced, one consumed)
+#pragma unroll
+  for (int i = 0; i < 2; ++i) p_a[i] = p_b[i] = u32x4{0, 0, 0, 0};
+
+  // rescale everything that is relative to the reference maximum: l, O and the packed P^T of
+  // the block whose PV product has not been issued yet
+  auto raise_reference = [&](float mx, u32x4 (&pend)[2]) __attribute__((always_inline)) {
+    const float m_new = fmaxf(m_ref, mx);
+    const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);  // exp2(-inf) = 0 on the first block
+    m_ref = m_new;
+    l_run *= alpha;
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb) oacc[cb] *= alpha;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const uint32_t u = pend[i][r];
+        pend[i][r] = pack_bf16(__uint_as_float(u << 16) * alpha, __uint_as_float(u & 0xffff0000u) * alpha);
+      }
+  };
+  auto block_max = [&](const f32x16& s) __attribute__((always_inline)) {
+    float mx = fmaxf(s[0], s[1]);
+#pragma unroll
+    for (int r = 2; r < 16; ++r) mx = fmaxf(mx, s[r]);
+    return attn_max_halves(mx) * c;
+  };
+
+  // ---- boundary-case building blocks (compiler-scheduled, not overlapped) ----------------------
+  auto qk_block = [&](f32x16& s, auto koff) __attribute__((always_inline)) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s[r] = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < NKK; ++kk)
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, k_operand(koff, kk)), qf[kk], s, 0, 0, 0);
+  };
+  auto pv_block = [&](const u32x4 (&pk)[2], auto voff) __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < 2 * NCB; ++i) {
+      const int cb = i % NCB, kc = i / NCB;
+      oacc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, v_operand(voff, cb, kc)),
+                                                         __builtin_bit_cast(bf16x8, pk[kc]), oacc[cb], 0, 0, 0);
+    }
+  };
+  auto softmax_block = [&](f32x16& s, u32x4 (&pk)[2], u32x4 (&pend)[2], int key0, bool need_mask) __attribute__((always_inline)) {
+    if (need_mask) {
+      const int kbase = key0 + 4 * h;
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        if (kbase + 8 * (r >> 2) + (r & 3) > limit) s[r] = -INFINITY;
+    }
+    const float mx = block_max(s);
+    if (__builtin_amdgcn_ballot_w64(mx > m_ref + kTau) != 0) raise_reference(mx, pend);
+    float ls0 = 0.f, ls1 = 0.f;
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+      const float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[2 * r], c, -m_ref));
+      const float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[2 * r + 1], c, -m_ref));
+      pk[r >> 2][r & 3] = pack_bf16(e0, e1);
+      ls0 += e0;
+      ls1 += e1;
+    }
+    l_run += ls0 + ls1;
+  };
+  auto is_active = [&](int key0) __attribute__((always_inline)) {
+    return wave_valid && key0 < kv_end && (!CAUSAL || key0 <= wlast);
+  };
+  auto needs_mask = [&](int key0) __attribute__((always_inline)) {
+    return (CAUSAL && key0 + 31 > wq0) || key0 + 31 >= N;
+  };
+
+  // ---- the pipelined step on fully visible blocks ------------------------------------------------
+  //   s_in  : scores of the block exponentiated now            -> p_out
+  //   s_out : scores of the next block, K operands at koff
+  //   p_pv  : probabilities of the previous block, multiplied into O with the V operands at voff
+  u32x4 ka[NQA];  // K operands of part A of the NEXT step, requested during part B of the current one
+  auto step_hot = [&](f32x16& s_in, f32x16& s_out, u32x4 (&p_out)[2], u32x4 (&p_pv)[2], auto koff, auto voff, auto knext) __attribute__((always_inline)) {
+    // -- part A: block maximum of s_in, interleaved with the first half of s_out = K Q^T
+    float mx = vmax3(s_in[0], s_in[1], s_in[2]);
+    mx = vmax3(mx, s_in[3], s_in[4]);
+    mx = vmax3(mx, s_in[5], s_in[6]);
+    mx = vmax3(mx, s_in[7], s_in[8]);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s_out[r] = 0.f;
+    s_out = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ka[0]), qf[0], s_out, 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    mx = vmax3(mx, s_in[9], s_in[10]);
+    mx = vmax3(mx, s_in[11], s_in[12]);
+    mx = vmax3(mx, s_in[13], s_in[14]);
+    mx = vmax2(mx, s_in[15]);
+#pragma unroll
+    for (int i = 1; i < NQA; ++i) {
+      s_out = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ka[i]), qf[i], s_out, 0, 0, 0);
+      if (i == 1) mx = vmax_halves(mx) * c;
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    // operands of the first RA MFMAs of part B
+    u32x4 opnd[NOPS];
+    auto read_op = [&](int m) __attribute__((always_inline)) {
+      if (m % 3 == 0) opnd[m] = k_operand(koff, NQA + m / 3);
+      else {
+        const int i = (m / 3) * 2 + (m % 3 - 1);
+        opnd[m] = v_operand(voff, i % NCB, i / NCB);
+      }
+    };
+#pragma unroll
+    for (int m = 0; m < RA; ++m) read_op(m);
+    __builtin_amdgcn_sched_barrier(0);
+    if (__builtin_amdgcn_ballot_w64(mx > m_ref + kTau) != 0) raise_reference(mx, p_pv);
+    __builtin_amdgcn_sched_barrier(0);
+    // -- part B: exponentials of s_in, interleaved with the rest of s_out and with O += V P
+    float e0[8], e1[8];
+    float ls0 = 0.f, ls1 = 0.f;
+    auto unit_front = [&](int u) __attribute__((always_inline)) {
+#ifdef ATTN_EXP_SKIP_VALU
+      e0[u] = s_in[2 * u]; e1[u] = s_in[2 * u + 1]; return;
+#endif
+      e0[u] = __builtin_amdgcn_exp2f(__builtin_fmaf(s_in[2 * u], c, -m_ref));
+      e1[u] = __builtin_amdgcn_exp2f(__builtin_fmaf(s_in[2 * u + 1], c, -m_ref));
+    };
+    auto unit_back = [&](int u) __attribute__((always_inline)) {
+#ifdef ATTN_EXP_SKIP_VALU
+      p_out[u >> 2][u & 3] = __float_as_uint(e0[u]) ^ __float_as_uint(e1[u]); return;
+#endif
+      p_out[u >> 2][u & 3] = pack_bf16(e0[u], e1[u]);
+      ls0 += e0[u];
+      ls1 += e1[u];
+    };
+#pragma unroll
+    for (int m = 0; m < NOPS; ++m) {
+      if (m % 3 == 0) {
+        s_out = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, opnd[m]), qf[NQA + m / 3], s_out, 0, 0, 0);
+      } else {
+        const int i = (m / 3) * 2 + (m % 3 - 1);
+        const int cb = i % NCB, kc = i / NCB;
+        oacc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, opnd[m]), __builtin_bit_cast(bf16x8, p_pv[kc]),
+                                                           oacc[cb], 0, 0, 0);
+      }
+      if (m + RA < NOPS) read_op(m + RA);
+      if (m >= NOPS - NQA - 2 && m < NOPS - 2) ka[m - (NOPS - NQA - 2)] = k_operand(knext, m - (NOPS - NQA - 2));
+      // the 8 exponential units (2 elements each) are spread evenly over the NOPS MFMAs
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        if (u * NOPS / 8 == m) {
+          unit_front(u);
+          if (u > 0) unit_back(u - 1);
+        }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    unit_back(7);
+    l_run += ls0 + ls1;
+  };
+
+  // the same step for blocks that may be masked or not visible to this wave (run-time offsets)
+  auto step_any = [&](bool do_sm, int key0, bool do_mm, f32x16& s_in, f32x16& s_out, u32x4 (&p_out)[2], u32x4 (&p_pv)[2], int koff,
+                      int voff) __attribute__((always_inline)) {
+    if (do_sm) softmax_block(s_in, p_out, p_pv, key0, needs_mask(key0));
+    if (do_mm) {
+      qk_block(s_out, koff);
+      pv_block(p_pv, voff);
+    }
+  };
+
+  // ---- prologue: block 0 ---------------------------------------------------------------------------
+  // key tile 0 (and Q) have landed once only the bundle loads issued after them are outstanding
+  if (nt > 1) ATTN_WAIT_VMCNT(4 * NLD);
+  else ATTN_WAIT_VMCNT(2 * NLD);
+#pragma unroll
+  for (int kk = 0; kk < NKK; ++kk) asm volatile("" ::"v"(qf[kk]));  // Q is in registers from here on
+  attn_wg_barrier();
+  if (wave_valid) {
+    qk_block(s_b, 2 * TILEB);                          // S(0)
+    softmax_block(s_b, p_b, p_a, 0, needs_mask(0));    // P(0) -> p_b (nothing pending yet)
+    qk_block(s_a, 2 * TILEB + SUBB);                   // S(1); ignored if block 1 is not visible
+  }
+  if (nt > 1) ATTN_WAIT_VMCNT(2 * NLD);
+  else ATTN_WAIT_VMCNT(0);
+  attn_wg_barrier();  // bundle 0 is full; the K part of slot 2 is empty again
+#pragma unroll
+  for (int i = 0; i < NQA; ++i) ka[i] = k_operand(0, i);  // part-A operands of the first pipelined step
+
+  // ---- main loop over bundles ------------------------------------------------------------------------
+  // iteration b: exponentiate blocks 2b+1 and 2b+2, compute the scores of blocks 2b+2 and 2b+3
+  // (key tile b+1), accumulate blocks 2b and 2b+1 (value tile b)
+  // between the two steps of iteration b: bundle b+1 (requested one iteration ago, the only
+  // loads in flight) is published, and the slot of bundle b-1, which every wave has finished
+  // reading, is handed to bundle b+2
+  auto bundle_mid = [&](int b, int free_slot) __attribute__((always_inline)) {
+    ATTN_WAIT_VMCNT(0);
+#ifndef ATTN_EXP_NOBAR
+    attn_wg_barrier();
+#endif
+    if (b + 2 < nt) issue_bundle(b + 2, free_slot);
+  };
+  auto bundle_hot = [&](int b, auto slot_tag) __attribute__((always_inline)) {
+    constexpr int SLOT = decltype(slot_tag)::value;
+    step_hot(s_a, s_b, p_a, p_b, ic<SLOT * TILEB>{}, ic<SLOT * TILEB>{}, ic<SLOT * TILEB + SUBB>{});
+    bundle_mid(b, (SLOT + 2) % NSLOT);
+    step_hot(s_b, s_a, p_b, p_a, ic<SLOT * TILEB + SUBB>{}, ic<SLOT * TILEB + SUBB>{}, ic<((SLOT + 1) % NSLOT) * TILEB>{});
+  };
+  auto bundle_any = [&](int b, int slot) __attribute__((always_inline)) {
+    const int k1 = (2 * b + 1) * 32, k2 = k1 + 32;
+    step_any(is_active(k1), k1, is_active(k1 - 32), s_a, s_b, p_a, p_b, slot * TILEB, slot * TILEB);
+    bundle_mid(b, slot >= 1 ? slot - 1 : NSLOT - 1);
+    step_any(is_active(k2), k2, is_active(k1), s_b, s_a, p_b, p_a, slot * TILEB + SUBB, slot * TILEB + SUBB);
+  };
+
+  // bundles 0 .. n_hot-1 touch only blocks (up to 2b+2) that every query of this wave sees in full
+  const int vis = CAUSAL ? min(wq0, N - 1) : N - 1;  // last key every query of the wave can see
+  int n_hot = (wave_valid && vis >= 95) ? (vis - 95) / 64 + 1 : 0;
+  n_hot -= n_hot % NSLOT;
+  int b = 0;
+  for (; b < n_hot; b += NSLOT) {
+    bundle_hot(b, ic<0>{});
+    bundle_hot(b + 1, ic<1>{});
+    bundle_hot(b + 2, ic<2>{});
+  }
+  for (int slot = 0; b < nt; ++b) {  // b is a multiple of NSLOT here, so the ring is at slot 0
+    bundle_any(b, slot);
+    slot = slot == NSLOT - 1 ? 0 : slot + 1;
+  }
+
+  // ---- epilogue: O = acc / l (bf16), lse = (m + log2 l) * ln 2 ------------------------------------------
+  char* const ohead = (char*)p.o + ((size_t)(tc.b * p.Hq + tc.hq) * N) * ROWB;
+  float* const lsehead = p.lse + (size_t)(tc.b * p.Hq + tc.hq) * N;
+  {
+    const float l = attn_sum_halves(l_run);
+    const float inv = p.out_scale / l;
+    if (qrow < N && h == 0) lsehead[qrow] = (m_ref + __builtin_amdgcn_logf(l)) * 0.6931471805599453f;
+    // lane (qi,h) holds O^T rows 32cb + 8b + 4h + r.  Exchange with the other half so that every
+    // lane owns 8 consecutive output columns 32cb + 16a + 8h + (0..7): one 16-byte store each.
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+      for (int a = 0; a < 2; ++a) {
+        uint32_t x[2], y[2];
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+          const uint32_t tx = pack_bf16(oacc[cb][(2 * a) * 4 + 2 * r] * inv, oacc[cb][(2 * a) * 4 + 2 * r + 1] * inv);
+          const uint32_t ty = pack_bf16(oacc[cb][(2 * a + 1) * 4 + 2 * r] * inv, oacc[cb][(2 * a + 1) * 4 + 2 * r + 1] * inv);
+          auto sw = __builtin_amdgcn_permlane32_swap(tx, ty, false, false);
+          x[r] = sw[0];
+          y[r] = sw[1];
+        }
+        if (qrow < N) {
+          u32x4 out = {x[0], x[1], y[0], y[1]};
+          *(u32x4*)(ohead + (size_t)qrow * ROWB + (cb * 32 + a * 16 + h * 8) * 2) = out;
+        }
+      }
+  }
+}
+
+template <int D>
+int launch_sp(const AttnParams& p, int grid, hipStream_t stream) {
+  if (p.causal) hipLaunchKernelGGL((attn_fwd_bf16_sp_kernel<D, true>), dim3(grid), dim3(512), 0, stream, p);
+  else hipLaunchKernelGGL((attn_fwd_bf16_sp_kernel<D, false>), dim3(grid), dim3(512), 0, stream, p);
+  return (int)hipGetLastError();
+}
+
+}  // namespace
+
+const AttnVariant* attn_bf16_sp_variants(int* count) {
+  static const AttnVariant table[] = {
+      {"bf16 d128 pipelined BM256 BN64", 0, 128, 256, 64, 512, 2 * 3 * 64 * 128 * 2, launch_sp<128>},
+      {"bf16 d64 pipelined BM256 BN64", 0, 64, 256, 64, 512, 2 * 3 * 64 * 64 * 2, launch_sp<64>},
+  };
+  *count = (int)(sizeof(table) / sizeof(table[0]));
+  return table;
+}

@@ -30,3 +30,4 @@ struct AttnVariant {
 // Variant tables, defined by the kernel translation units (host functions).
 const AttnVariant* attn_bf16_variants(int* count);
 const AttnVariant* attn_bf16_pp_variants(int* count);
+const AttnVariant* attn_bf16_sp_variants(int* count);
