@@ -7,7 +7,11 @@ quoted on: B=2, Hq=Hkv=32, N=8192, d=128, bf16, non-causal, synthetic N(0,1)*0.5
 inputs already resident in HBM.  Prints ONE JSON line on stdout.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--config I] [--variant V]
-                  [--no-cpu-baseline] [--all-configs]
+                  [--no-cpu-baseline] [--all-configs] [--copy-calibration]
+
+--copy-calibration runs nothing but a 1 GiB device-to-device copy (three times): under
+`rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE` it gives the factor that converts those
+counters into bytes (see profiles/).
 """
 from __future__ import annotations
 
@@ -113,12 +117,13 @@ def cpu_baseline(cfg, inp, budget_s=20.0):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=25)  # ~50 ms: the shader clock needs about that long to settle
     ap.add_argument("--config", type=int, default=2, help="index into workloads.CONFIGS (default: the headline config)")
     ap.add_argument("--variant", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--all-configs", action="store_true", help="also time the other bf16 configs (reported in 'others')")
+    ap.add_argument("--copy-calibration", action="store_true", help="only run a 1 GiB copy (counter calibration)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (every (batch, head) is independent, so the path would "
@@ -130,6 +135,15 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": 1 << 30, "copy_bytes_written": 1 << 30, "launches": 3}))
+        return
+
     import paper_2605_10905_amd as A
     import workloads as wl
 

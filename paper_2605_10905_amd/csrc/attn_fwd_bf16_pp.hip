@@ -95,7 +95,7 @@ __device__ long long g_phase_timing[8][4];
 
 constexpr float kTau = 8.0f;  // the running max may lag a block max by up to 2^8 before a rescale
 
-template <int D, bool CAUSAL>
+template <int D, bool CAUSAL, int NSLOT>
 __global__ void __launch_bounds__(512, 2) attn_fwd_bf16_pp_kernel(const AttnParams p) {
   constexpr int BN = 64, NWAVES = 8, BM = NWAVES * 32, NT = NWAVES * 64;
   constexpr int NKK = D / 16;       // MFMA k-steps over the head dimension
@@ -104,11 +104,12 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_bf16_pp_kernel(const AttnPara
   constexpr int NCH = ROWB / 16;    // 16-byte chunks per row
   constexpr int TILEB = BN * ROWB;  // bytes per K (or V) tile
   constexpr int SUBB = 32 * ROWB;   // bytes per 32-key block
-  constexpr int NSLOT = 3;
+  constexpr int PD = NSLOT - 1;  // tiles requested ahead of the one being consumed
   constexpr int VBASE = NSLOT * TILEB;  // K slots first, then V slots
   constexpr int NLD = BN * NCH / NT;    // direct-to-LDS loads per thread per tile per tensor
   static_assert(BN * NCH % NT == 0 && NLD >= 1, "tile must divide evenly over the workgroup");
-  static_assert(VBASE < 65536, "LDS immediates must fit 16 bits");
+  static_assert((NSLOT - 1) * TILEB + SUBB + 16 * ROWB < 65536, "ring offsets must fit the 16-bit LDS immediate");
+  static_assert(NSLOT == 3 || NSLOT == 4, "ring depth");
 
   // static allocation: the ring then sits at a link-time-known LDS address and every ring
   // offset folds into the 16-bit immediate of the LDS instructions
@@ -180,6 +181,7 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_bf16_pp_kernel(const AttnPara
     for (int kk = 0; kk < NKK; ++kk) qf[kk] = *(const bf16x8*)(src + kk * 32);
   }
   if (nt > 1) issue_tile_loads(1, 1);
+  if (PD > 2 && nt > 2) issue_tile_loads(2, 2);
 
   // ---- LDS read addresses (slot 0, first 32-key block) ---------------------------------
   uint32_t kaddr[NKK];
@@ -339,8 +341,9 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_bf16_pp_kernel(const AttnPara
     }
   };
 
-  // tile 0 (and Q) have landed once at most the loads of tile 1 are outstanding
-  if (nt > 1) WAIT_VMCNT(2 * NLD);
+  // tile 0 (and Q) have landed once only the loads of the later tiles are outstanding
+  if (PD > 2 && nt > 2) WAIT_VMCNT(4 * NLD);
+  else if (nt > 1) WAIT_VMCNT(2 * NLD);
   else WAIT_VMCNT(0);
 #pragma unroll
   for (int kk = 0; kk < NKK; ++kk) asm volatile("" ::"v"(qf[kk]));  // Q is in registers from here on
@@ -356,10 +359,13 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_bf16_pp_kernel(const AttnPara
   // waited for at the end of the first VALU phase of tile j+1, so that the barrier closing
   // that phase publishes it
   auto prefetch = [&](int j, int slot) __attribute__((always_inline)) {
-    if (j + 2 < nt) issue_tile_loads(j + 2, slot);
+    if (j + PD < nt) issue_tile_loads(j + PD, slot);
   };
-  // tile j+1 was requested four phases ago; its loads are the only ones in flight here
-  auto publish_wait = [&]() __attribute__((always_inline)) { WAIT_VMCNT(0); };
+  // tile j+1 must have landed; with a four-slot ring the loads of tile j+2 may stay in flight
+  auto publish_wait = [&](int j) __attribute__((always_inline)) {
+    if (PD > 2 && j + 2 < nt) WAIT_VMCNT(2 * NLD);
+    else WAIT_VMCNT(0);
+  };
 
   // A tile whose 64 keys are visible to every query of the wave: straight-line code, all
   // LDS offsets are immediates (SLOT is a compile-time constant).
@@ -377,11 +383,11 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_bf16_pp_kernel(const AttnPara
     // first 32 keys
     valu_phase(0, false);
     read_ahead(v0off, k1off);
-    publish_wait();
+    publish_wait(j);
     PT_ADD(0, tp);
     wg_barrier();
     PT_ADD(1, tp);
-    prefetch(j, (SLOT + 2) % NSLOT);
+    prefetch(j, (SLOT + PD) % NSLOT);
     __builtin_amdgcn_s_setprio(1);
     mfma_phase_ra(v0off, k1off);
     __builtin_amdgcn_s_setprio(0);
@@ -410,7 +416,7 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_bf16_pp_kernel(const AttnPara
       const int key0 = j * BN + kb * 32;
       const bool active = is_active(key0);
       if (active) valu_phase(key0, (CAUSAL && key0 + 31 > wq0) || key0 + 31 >= N);
-      if (kb == 0) publish_wait();
+      if (kb == 0) publish_wait(j);
       wg_barrier();
       if (kb == 0) prefetch(j, slot >= 1 ? slot - 1 : NSLOT - 1);
       if (active) {
@@ -431,6 +437,7 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_bf16_pp_kernel(const AttnPara
     tile_hot(j, std::integral_constant<int, 0>{});
     tile_hot(j + 1, std::integral_constant<int, 1>{});
     tile_hot(j + 2, std::integral_constant<int, 2>{});
+    if (NSLOT > 3) tile_hot(j + 3, std::integral_constant<int, 3 % NSLOT>{});
   }
   for (int slot = 0; j < nt; ++j) {  // j is a multiple of NSLOT here, so the ring is at slot 0
     tile_any(j, slot);
@@ -473,10 +480,10 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_bf16_pp_kernel(const AttnPara
   }
 }
 
-template <int D>
+template <int D, int NSLOT>
 int launch_pp(const AttnParams& p, int grid, hipStream_t stream) {
-  if (p.causal) hipLaunchKernelGGL((attn_fwd_bf16_pp_kernel<D, true>), dim3(grid), dim3(512), 0, stream, p);
-  else hipLaunchKernelGGL((attn_fwd_bf16_pp_kernel<D, false>), dim3(grid), dim3(512), 0, stream, p);
+  if (p.causal) hipLaunchKernelGGL((attn_fwd_bf16_pp_kernel<D, true, NSLOT>), dim3(grid), dim3(512), 0, stream, p);
+  else hipLaunchKernelGGL((attn_fwd_bf16_pp_kernel<D, false, NSLOT>), dim3(grid), dim3(512), 0, stream, p);
   return (int)hipGetLastError();
 }
 
@@ -490,8 +497,9 @@ extern "C" int attn_debug_phase_timing(long long* out) {
 
 const AttnVariant* attn_bf16_pp_variants(int* count) {
   static const AttnVariant table[] = {
-      {"bf16 d128 ping-pong BM256 BN64", 0, 128, 256, 64, 512, 2 * 3 * 64 * 128 * 2, launch_pp<128>},
-      {"bf16 d64 ping-pong BM256 BN64", 0, 64, 256, 64, 512, 2 * 3 * 64 * 64 * 2, launch_pp<64>},
+      {"bf16 d128 ping-pong BM256 BN64 ring4", 0, 128, 256, 64, 512, 2 * 4 * 64 * 128 * 2, launch_pp<128, 4>},
+      {"bf16 d64 ping-pong BM256 BN64 ring4", 0, 64, 256, 64, 512, 2 * 4 * 64 * 64 * 2, launch_pp<64, 4>},
+      {"bf16 d128 ping-pong BM256 BN64 ring3", 0, 128, 256, 64, 512, 2 * 3 * 64 * 128 * 2, launch_pp<128, 3>},
   };
   *count = (int)(sizeof(table) / sizeof(table[0]));
   return table;
