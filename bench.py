@@ -27,6 +27,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_TFLOPS = {"bf16": 2516.6, "fp8_e4m3": 5033.2}  # 256 CUs x 2.4 GHz x 4096 (8192) flop/clk/CU, dense
+# HBM bytes per launch measured with rocprofv3 (FETCH_SIZE x 2.0 KiB + WRITE_SIZE x 1.0 KiB, factors from
+# a 1 GiB copy); the runs and figures are in profiles/.  None where no such run has been made.
+MEASURED_TRAFFIC_BYTES = {"long_noncausal_8k": 5.392e8}
 
 
 def log(*a):
@@ -174,7 +177,7 @@ def main():
                    "variant": A.attn_variant_name(args.variant) if args.variant is not None else "library default",
                    "pct_of_dense_peak": 100 * tflops / peak},
         "roofline": {"bound": "mfma", "achieved": kern_tflops, "peak": peak, "unit": "TFLOP/s", "frac": kern_tflops / peak,
-                     "traffic": None,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(cfg["name"]) if args.variant is None else None,
                      "kernel_ms_avg": r["kern_ms_avg"], "algorithmic_flop_per_launch": r["flops"]},
     }
     if args.all_configs:

@@ -2,22 +2,25 @@
 
 The Python layer only marshals arguments: every step of the path runs in the
 HIP kernels of libattn_mi355x.so.  There is no CPU or PyTorch fallback; if the
-library is missing, importing `paper_2605_10905_amd.binding` raises.
+library is missing, the first use of any binding name raises.
+
+The binding is imported on first attribute access, so that
+`python -m paper_2605_10905_amd.build` can rebuild a missing or broken library.
 """
-from .binding import (  # noqa: F401
-    ATTN_BF16,
-    ATTN_FP8_E4M3,
-    AttnError,
-    attn_fwd,
-    attn_fwd_fp8,
-    attn_fwd_variant,
-    attn_num_variants,
-    attn_num_workgroups,
-    attn_status_string,
-    attn_tile_coord,
-    attn_variant_bm,
-    attn_variant_name,
-    attn_version,
-    lib,
-    lib_path,
+import importlib
+
+_NAMES = (
+    "ATTN_BF16", "ATTN_FP8_E4M3", "AttnError", "attn_fwd", "attn_fwd_fp8", "attn_fwd_variant", "attn_num_variants",
+    "attn_num_workgroups", "attn_status_string", "attn_tile_coord", "attn_variant_bm", "attn_variant_name", "attn_version",
+    "lib", "lib_path",
 )
+
+
+def __getattr__(name):
+    if name in _NAMES:
+        return getattr(importlib.import_module(".binding", __name__), name)
+    raise AttributeError(f"module {__name__!r} has no attribute {name!r}")
+
+
+def __dir__():
+    return sorted(list(globals()) + list(_NAMES))

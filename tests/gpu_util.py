@@ -113,3 +113,16 @@ def check_sampled(inp, o, lse, heads, rows_per_head, label=""):
     assert worst["rel_fro"] <= tol["rel_fro"], f"{label}: {worst}"
     assert worst["lse_max_abs"] <= tol["lse"], f"{label}: {worst}"
     return worst
+
+
+def check_whole_head(inp, o, lse, b, h, label=""):
+    """Full-size check of ONE whole (b, h) slice: every row of that head against the oracle."""
+    x = decode(inp)
+    g = h // (inp["Hq"] // inp["Hkv"])
+    o_ref, lse_ref = orc.attn_head(x["q"][b, h], x["k"][b, g], x["v"][b, g], inp["causal"], inp["scale"])
+    m = orc.error_metrics(o_to_f64(o[b, h]), o_ref, lse[b, h].cpu().numpy().astype(np.float64), lse_ref)
+    tol = TOL[inp["dtype"]]
+    assert m["max_abs"] <= tol["max_abs"], f"{label}: {m}"
+    assert m["rel_fro"] <= tol["rel_fro"], f"{label}: {m}"
+    assert m["lse_max_abs"] <= tol["lse"], f"{label}: {m}"
+    return m
