@@ -18,11 +18,14 @@
 //     newest tile lets those stay in flight while the older tile is published by
 //     the next barrier ("full"); a slot is overwritten only after the barrier that
 //     ends the last phase reading it ("empty").  stage = tile mod 3.
-//   * The running maximum is only raised when a row's block maximum exceeds it by
-//     more than a threshold (exact: any reference value is valid for the streaming
-//     softmax as long as nothing overflows; exponent arguments stay <= threshold).
-//     The accumulator rescale therefore runs once or twice per row instead of once
-//     per tile.
+//   * No block maximum is taken on the common path.  The exponentials of a block are
+//     computed against the CURRENT reference maximum; only when a lane's partial row sum
+//     comes out large (or not a number, as on the very first block where the reference
+//     is -inf) is the true block maximum taken, the reference raised, the accumulator
+//     rescaled and the block redone.  This is exact: any reference value is valid for
+//     the streaming softmax as long as nothing overflows.  The rescale then runs once
+//     or twice per row instead of once per tile, and the per-score vector work is one
+//     multiply-add, one exponential, one add and half a pack.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -93,7 +96,10 @@ __device__ long long g_phase_timing[8][4];
 #define PT_ADD(slot, t0) do { } while (0)
 #endif
 
-constexpr float kTau = 8.0f;  // the running max may lag a block max by up to 2^8 before a rescale
+// A lane's partial row sum of one 32-key block (16 exponentials) above this sends the block
+// through the slow pass that raises the reference maximum; below it every exponential is
+// < 2^16 and fp32 / bf16 ranges are nowhere near.
+constexpr float kSumLimit = 65536.0f;
 
 template <int D, bool CAUSAL, int NSLOT>
 __global__ void __launch_bounds__(512, 2) attn_fwd_bf16_pp_kernel(const AttnParams p) {
@@ -249,31 +255,50 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_bf16_pp_kernel(const AttnPara
       for (int r = 0; r < 16; ++r)
         if (kbase + 8 * (r >> 2) + (r & 3) > limit) s[r] = -INFINITY;
     }
-    float mx = fmaxf(s[0], s[1]);
+    // Optimistic pass: exponentials relative to the CURRENT reference maximum, no block
+    // maximum taken.  Any reference is valid for the streaming softmax as long as nothing
+    // overflows, so the pass stands unless some lane's partial sum is large (or not a
+    // number: the first block starts from m_ref = -inf and always lands in the slow pass).
+    f32x16 e;
 #pragma unroll
-    for (int r = 2; r < 16; ++r) mx = fmaxf(mx, s[r]);
-    mx = max_halves(mx) * c;
-    if (__builtin_amdgcn_ballot_w64(mx > m_ref + kTau) != 0) {
+    for (int r = 0; r < 16; ++r) e[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c, -m_ref));
+    float ls0 = e[0], ls1 = e[1];
+#pragma unroll
+    for (int r = 1; r < 8; ++r) {
+      ls0 += e[2 * r];
+      ls1 += e[2 * r + 1];
+    }
+    float ls = ls0 + ls1;
+    if (__builtin_amdgcn_ballot_w64(!(ls <= kSumLimit)) != 0) {
+      // slow pass: raise the reference to the true block maximum, rescale, redo the block
+      float mx = fmaxf(s[0], s[1]);
+#pragma unroll
+      for (int r = 2; r < 16; ++r) mx = fmaxf(mx, s[r]);
+      mx = max_halves(mx) * c;
       const float m_new = fmaxf(m_ref, mx);
       const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);  // exp2(-inf) = 0 on the first block
       m_ref = m_new;
       l_run *= alpha;
 #pragma unroll
       for (int cb = 0; cb < NCB; ++cb) oacc[cb] *= alpha;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) e[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c, -m_ref));
+      ls0 = e[0], ls1 = e[1];
+#pragma unroll
+      for (int r = 1; r < 8; ++r) {
+        ls0 += e[2 * r];
+        ls1 += e[2 * r + 1];
+      }
+      ls = ls0 + ls1;
     }
-    float ls0 = 0.f, ls1 = 0.f;
 #pragma unroll
     for (int r = 0; r < 8; ++r) {
-      const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[2 * r], c, -m_ref));
-      const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[2 * r + 1], c, -m_ref));
       bf16x2 t;
-      t[0] = (__bf16)p0;
-      t[1] = (__bf16)p1;
+      t[0] = (__bf16)e[2 * r];
+      t[1] = (__bf16)e[2 * r + 1];
       pk[r >> 2][r & 3] = __builtin_bit_cast(uint32_t, t);
-      ls0 += p0;
-      ls1 += p1;
     }
-    l_run += ls0 + ls1;
+    l_run += ls;
     // everything above belongs to this phase: keep the compiler from sinking the
     // exponentials past the phase barrier into the matrix phase
     asm volatile("" : "+v"(pk[0]), "+v"(pk[1]), "+v"(l_run));
@@ -497,9 +522,9 @@ extern "C" int attn_debug_phase_timing(long long* out) {
 
 const AttnVariant* attn_bf16_pp_variants(int* count) {
   static const AttnVariant table[] = {
-      {"bf16 d128 ping-pong BM256 BN64 ring4", 0, 128, 256, 64, 512, 2 * 4 * 64 * 128 * 2, launch_pp<128, 4>},
-      {"bf16 d64 ping-pong BM256 BN64 ring4", 0, 64, 256, 64, 512, 2 * 4 * 64 * 64 * 2, launch_pp<64, 4>},
       {"bf16 d128 ping-pong BM256 BN64 ring3", 0, 128, 256, 64, 512, 2 * 3 * 64 * 128 * 2, launch_pp<128, 3>},
+      {"bf16 d64 ping-pong BM256 BN64 ring4", 0, 64, 256, 64, 512, 2 * 4 * 64 * 64 * 2, launch_pp<64, 4>},
+      {"bf16 d128 ping-pong BM256 BN64 ring4", 0, 128, 256, 64, 512, 2 * 4 * 64 * 128 * 2, launch_pp<128, 4>},
   };
   *count = (int)(sizeof(table) / sizeof(table[0]));
   return table;
