@@ -101,6 +101,13 @@ __device__ long long g_phase_timing[8][4];
 // < 2^16 and fp32 / bf16 ranges are nowhere near.
 constexpr float kSumLimit = 65536.0f;
 
+#ifndef ATTN_PP_FULLRA
+#define ATTN_PP_FULLRA 1
+#endif
+#ifndef ATTN_PP_RA_EARLY
+#define ATTN_PP_RA_EARLY 1
+#endif
+
 template <int D, bool CAUSAL, int NSLOT>
 __global__ void __launch_bounds__(512, 2) attn_fwd_bf16_pp_kernel(const AttnParams p) {
   constexpr int BN = 64, NWAVES = 8, BM = NWAVES * 32, NT = NWAVES * 64;
@@ -245,6 +252,7 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_bf16_pp_kernel(const AttnPara
   // VALU phase: mask, row max, (rare) rescale, P = exp2(c S - m_ref), row sum
   auto valu_phase = [&](int key0, bool need_mask) __attribute__((always_inline)) {
 #ifdef ATTN_EXP_SKIP_VALU
+    asm volatile("" ::"v"(s));  // the scores stay live, so the QK^T MFMAs are kept
     pk[0] = u32x4{0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u}; pk[1] = pk[0]; l_run += 1.f; m_ref = 0.f;
     asm volatile("" : "+v"(pk[0]), "+v"(pk[1]), "+v"(l_run));
     return;
@@ -350,6 +358,10 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_bf16_pp_kernel(const AttnPara
   // (independent accumulators, so neither waits for the other), then requests the operands of
   // step i + KP into the registers it has just freed.
   auto mfma_phase_ra = [&](auto voff, auto koff) __attribute__((always_inline)) {
+#ifdef ATTN_EXP_SKIP_MFMA
+    asm volatile("" : "+v"(s));
+    return;
+#endif
     static_assert(NKK == 2 * NCB && KP == NCB, "step pairing assumes D/16 QK steps and 2*D/32 PV steps");
 #pragma unroll
     for (int r = 0; r < 16; ++r) s[r] = 0.f;
@@ -362,6 +374,29 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_bf16_pp_kernel(const AttnPara
         kpre[i] = *(LDS_AS bf16x8*)(smem + kaddr[i + KP] + koff);
         vpre[cb] = v_operand(voff, cb, 1);
       }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+
+  // Variant with every operand of the phase read ahead (the vector phase has the slack to
+  // carry all the LDS reads): the matrix phase is then 2*NKK MFMAs back to back, no LDS wait.
+  bf16x8 kall[NKK];
+  s16x8 vall[NKK];
+  auto read_all = [&](auto voff, auto koff) __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < NKK; ++i) {
+      kall[i] = *(LDS_AS bf16x8*)(smem + kaddr[i] + koff);
+      vall[i] = v_operand(voff, i % NCB, i / NCB);
+    }
+  };
+  auto mfma_burst = [&]() __attribute__((always_inline)) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s[r] = 0.f;
+#pragma unroll
+    for (int i = 0; i < NKK; ++i) {
+      const int cb = i % NCB, kc = i / NCB;
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kall[i], qf[i], s, 0, 0, 0);
+      oacc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vall[i]), __builtin_bit_cast(bf16x8, pk[kc]), oacc[cb], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
     }
   };
@@ -406,27 +441,47 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_bf16_pp_kernel(const AttnPara
     constexpr std::integral_constant<int, SLOT * TILEB + SUBB> v1off{}, k1off{};
     constexpr std::integral_constant<int, ((SLOT + 1) % NSLOT) * TILEB> knoff{};
     // first 32 keys
+#if ATTN_PP_FULLRA
+    if (ATTN_PP_RA_EARLY) { read_all(v0off, k1off); __builtin_amdgcn_sched_barrier(0); }
+    valu_phase(0, false);
+    if (!ATTN_PP_RA_EARLY) read_all(v0off, k1off);
+#else
     valu_phase(0, false);
     read_ahead(v0off, k1off);
+#endif
     publish_wait(j);
     PT_ADD(0, tp);
     wg_barrier();
     PT_ADD(1, tp);
     prefetch(j, (SLOT + PD) % NSLOT);
     __builtin_amdgcn_s_setprio(1);
+#if ATTN_PP_FULLRA
+    mfma_burst();
+#else
     mfma_phase_ra(v0off, k1off);
+#endif
     __builtin_amdgcn_s_setprio(0);
     PT_ADD(2, tp);
     wg_barrier();
     PT_ADD(3, tp);
     // second 32 keys; the S^T computed here belongs to the first block of tile j+1
+#if ATTN_PP_FULLRA
+    if (ATTN_PP_RA_EARLY) { read_all(v1off, knoff); __builtin_amdgcn_sched_barrier(0); }
+    valu_phase(0, false);
+    if (!ATTN_PP_RA_EARLY) read_all(v1off, knoff);
+#else
     valu_phase(0, false);
     read_ahead(v1off, knoff);
+#endif
     PT_ADD(0, tp);
     wg_barrier();
     PT_ADD(1, tp);
     __builtin_amdgcn_s_setprio(1);
+#if ATTN_PP_FULLRA
+    mfma_burst();
+#else
     mfma_phase_ra(v1off, knoff);
+#endif
     __builtin_amdgcn_s_setprio(0);
     PT_ADD(2, tp);
     wg_barrier();

@@ -8,15 +8,15 @@
 // Orchestration.  All 8 waves of a workgroup run the same instruction stream, and that
 // stream is pipelined over 32-key blocks so that the matrix pipe and the vector pipe are fed
 // from the SAME wave at the same time (measured on gfx950: a wave that issues only MFMAs and
-// a second wave that issues only VALU work overlap poorly, because the vector wave gets an
-// issue slot only every ~9 cycles; one MFMA followed by four to five independent VALU
-// instructions from the same wave is nearly free).  In the step that handles block u a wave
+// a sibling that issues only VALU work delay each other at the shared issue port; one MFMA
+// followed by three to five independent VALU instructions from the same wave is nearly
+// free).  In the step that handles block u a wave
 //     * exponentiates block u            (VALU:  P(u)   = exp2(c S(u) - m))
 //     * computes the scores of block u+1 (MFMA:  S(u+1) = K(u+1) Q^T)
 //     * accumulates block u-1            (MFMA:  O^T   += V(u-1)^T P(u-1)^T)
-// and the three instruction streams are interleaved by hand (program order pinned with
-// scheduling barriers): every MFMA is followed by its share of the exponentials and by the
-// LDS reads of the operands three MFMAs ahead.
+// The three streams are independent inside a step; a scheduling-group pipeline at the end of
+// the step tells the compiler's scheduler the interleave: per MFMA one exponential, two or
+// three plain vector instructions and the LDS reads of the operand a few MFMAs ahead.
 //
 // K/V streaming.  Block u+1 of K and block u-1 of V travel together: "bundle" b holds key
 // tile b+1 and value tile b (64 keys each) and is consumed by exactly one loop iteration, so
@@ -25,10 +25,11 @@
 // signal of bundle b-1 (stage = b mod 3).  The barrier sits between the two 32-key steps of an
 // iteration so that the first K operands of the next iteration can be read one step early.
 //
-// The running maximum is raised only when a block maximum exceeds it by more than 2^8
-// (exact: any reference value is valid as long as nothing overflows), so the accumulator
-// rescale runs once or twice per row; when it does, the already-packed probabilities of the
-// block still waiting for its PV product are rescaled with it.
+// No block maximum is taken on the common path: exponentials are computed against the
+// current reference maximum, and only when a lane's partial row sum comes out large (or not a
+// number, as on the very first block) is the true block maximum taken, the reference raised,
+// the accumulator rescaled and the block redone (exact: any reference is valid for the
+// streaming softmax as long as nothing overflows).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -41,6 +42,7 @@
 namespace {
 
 constexpr float kTau = 8.0f;
+constexpr float kSumLimit = 65536.0f;  // a lane's 16-term partial sum above this redoes the block with a raised reference
 
 template <int V>
 using ic = std::integral_constant<int, V>;
@@ -52,20 +54,18 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
   return __builtin_bit_cast(uint32_t, t);
 }
 
-// max without the NaN-canonicalising self-max the compiler adds around fmaxf of MFMA results
-__device__ __forceinline__ float vmax3(float a, float b, float c) {
-  float d;
-  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "v"(b), "v"(c));
-  return d;
-}
-__device__ __forceinline__ float vmax2(float a, float b) {
-  float d;
-  asm("v_max_f32 %0, %1, %2" : "=v"(d) : "v"(a), "v"(b));
-  return d;
-}
-__device__ __forceinline__ float vmax_halves(float x) {
-  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  return vmax2(__uint_as_float(r[0]), __uint_as_float(r[1]));
+// Scheduling-group pipeline of one pipelined step (the builtin wants literal constants, hence the
+// recursion): per MFMA its share of the plain vector work, of the 16 exponentials, and the LDS
+// reads of the operand RA MFMAs ahead (one 128-bit K read or two transposing V reads).
+template <int M, int NM, int RA, int NVALU>
+__device__ __forceinline__ void step_pipeline() {
+  if constexpr (M < NM) {
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                         // MFMA
+    __builtin_amdgcn_sched_group_barrier(0x002, (NVALU * (M + 1)) / NM - (NVALU * M) / NM, 0);  // VALU
+    __builtin_amdgcn_sched_group_barrier(0x400, 16 / NM, 0);                                   // transcendental
+    __builtin_amdgcn_sched_group_barrier(0x100, ((M + RA) & 1) ? 2 : 1, 0);                    // LDS read
+    step_pipeline<M + 1, NM, RA, NVALU>();
+  }
 }
 
 template <int D, bool CAUSAL>
@@ -80,14 +80,12 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_bf16_sp_kernel(const AttnPara
   constexpr int NSLOT = 3;
   constexpr int VBASE = NSLOT * TILEB;  // K parts of the slots first, then the V parts
   constexpr int NLD = BN * NCH / NT;    // direct-to-LDS loads per thread per tile
-  constexpr int NQA = NKK / 2;          // QK^T steps issued before the rescale check
-  constexpr int NOPS = 3 * (NKK - NQA); // MFMAs after it: one QK^T step, then two PV steps, repeated
 #ifndef ATTN_RA
-#define ATTN_RA 5
+#define ATTN_RA 4
 #endif
   constexpr int RA = ATTN_RA;           // operands are read from LDS this many MFMAs ahead
   static_assert(BN * NCH % NT == 0 && NLD >= 1, "tile must divide evenly over the workgroup");
-  static_assert(2 * NCB == 2 * (NKK - NQA), "two PV steps per late QK^T step");
+  static_assert(NKK == 2 * NCB && RA >= 2 && RA <= 2 * NKK, "one PV step per QK^T step; read-ahead within a step");
   static_assert(NSLOT * TILEB < 65536, "ring offsets must fit the 16-bit LDS immediate");
 
   __shared__ __attribute__((aligned(1024))) char smem_raw[2 * NSLOT * TILEB];
@@ -283,85 +281,77 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_bf16_sp_kernel(const AttnPara
   };
 
   // ---- the pipelined step on fully visible blocks ------------------------------------------------
-  //   s_in  : scores of the block exponentiated now            -> p_out
-  //   s_out : scores of the next block, K operands at koff
-  //   p_pv  : probabilities of the previous block, multiplied into O with the V operands at voff
-  u32x4 ka[NQA];  // K operands of part A of the NEXT step, requested during part B of the current one
-  auto step_hot = [&](f32x16& s_in, f32x16& s_out, u32x4 (&p_out)[2], u32x4 (&p_pv)[2], auto koff, auto voff, auto knext) __attribute__((always_inline)) {
-    // -- part A: block maximum of s_in, interleaved with the first half of s_out = K Q^T
-    float mx = vmax3(s_in[0], s_in[1], s_in[2]);
-    mx = vmax3(mx, s_in[3], s_in[4]);
-    mx = vmax3(mx, s_in[5], s_in[6]);
-    mx = vmax3(mx, s_in[7], s_in[8]);
+  //   s_in  : scores of the block exponentiated now                     -> p_out
+  //   s_out : scores of the next block        (K operands at off)
+  //   p_pv  : probabilities of the previous block, multiplied into O    (V operands at off)
+  // The 2*NKK MFMAs alternate between the two products (the QK^T chain is dependent, the PV
+  // accumulators are not), operands are read from LDS RA MFMAs ahead; the first RA operands of a
+  // step are requested by the previous step (offnext = where the next step reads).
+  // The vector work needs no block maximum: exponentials are taken against the current
+  // reference and the block is redone, after raising the reference and rescaling, only if a
+  // lane's partial sum comes out large or not a number (always on the very first block).
+  // Source order inside the step does not matter: the scheduling-group pipeline at its end
+  // tells the scheduler how to interleave the four instruction classes.
+  constexpr int NM = 2 * NKK;
+  u32x4 pre[RA];
+  auto step_operand = [&](auto off, int m) __attribute__((always_inline)) {
+    const int i = m >> 1;
+    return (m & 1) ? v_operand(off, i % NCB, i / NCB) : k_operand(off, i);
+  };
+  auto exp_block = [&](const f32x16& s_in, u32x4 (&p_out)[2]) __attribute__((always_inline)) {
+    f32x16 e;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) e[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s_in[r], c, -m_ref));
+#pragma unroll
+    for (int u = 0; u < 8; ++u) p_out[u >> 2][u & 3] = pack_bf16(e[2 * u], e[2 * u + 1]);
+    float ls0 = e[0], ls1 = e[1];
+#pragma unroll
+    for (int u = 1; u < 8; ++u) {
+      ls0 += e[2 * u];
+      ls1 += e[2 * u + 1];
+    }
+    return ls0 + ls1;
+  };
+  auto step_hot = [&](f32x16& s_in, f32x16& s_out, u32x4 (&p_out)[2], u32x4 (&p_pv)[2], auto off, auto offnext) __attribute__((always_inline)) {
+    u32x4 op[NM];
+#pragma unroll
+    for (int m = 0; m < RA; ++m) op[m] = pre[m];
 #pragma unroll
     for (int r = 0; r < 16; ++r) s_out[r] = 0.f;
-    s_out = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ka[0]), qf[0], s_out, 0, 0, 0);
-    __builtin_amdgcn_sched_barrier(0);
-    mx = vmax3(mx, s_in[9], s_in[10]);
-    mx = vmax3(mx, s_in[11], s_in[12]);
-    mx = vmax3(mx, s_in[13], s_in[14]);
-    mx = vmax2(mx, s_in[15]);
 #pragma unroll
-    for (int i = 1; i < NQA; ++i) {
-      s_out = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ka[i]), qf[i], s_out, 0, 0, 0);
-      if (i == 1) mx = vmax_halves(mx) * c;
-      __builtin_amdgcn_sched_barrier(0);
+    for (int m = 0; m < NM; ++m) {
+      const int i = m >> 1;
+      if (m & 1)
+        oacc[i % NCB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, op[m]), __builtin_bit_cast(bf16x8, p_pv[i / NCB]),
+                                                                oacc[i % NCB], 0, 0, 0);
+      else
+        s_out = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, op[m]), qf[i], s_out, 0, 0, 0);
+      if (m + RA < NM) op[m + RA] = step_operand(off, m + RA);
+      else pre[m + RA - NM] = step_operand(offnext, m + RA - NM);
     }
-    // operands of the first RA MFMAs of part B
-    u32x4 opnd[NOPS];
-    auto read_op = [&](int m) __attribute__((always_inline)) {
-      if (m % 3 == 0) opnd[m] = k_operand(koff, NQA + m / 3);
-      else {
-        const int i = (m / 3) * 2 + (m % 3 - 1);
-        opnd[m] = v_operand(voff, i % NCB, i / NCB);
-      }
-    };
-#pragma unroll
-    for (int m = 0; m < RA; ++m) read_op(m);
-    __builtin_amdgcn_sched_barrier(0);
-    if (__builtin_amdgcn_ballot_w64(mx > m_ref + kTau) != 0) raise_reference(mx, p_pv);
-    __builtin_amdgcn_sched_barrier(0);
-    // -- part B: exponentials of s_in, interleaved with the rest of s_out and with O += V P
-    float e0[8], e1[8];
-    float ls0 = 0.f, ls1 = 0.f;
-    auto unit_front = [&](int u) __attribute__((always_inline)) {
 #ifdef ATTN_EXP_SKIP_VALU
-      e0[u] = s_in[2 * u]; e1[u] = s_in[2 * u + 1]; return;
+    asm volatile("" ::"v"(s_in));
+    return;
 #endif
-      e0[u] = __builtin_amdgcn_exp2f(__builtin_fmaf(s_in[2 * u], c, -m_ref));
-      e1[u] = __builtin_amdgcn_exp2f(__builtin_fmaf(s_in[2 * u + 1], c, -m_ref));
-    };
-    auto unit_back = [&](int u) __attribute__((always_inline)) {
-#ifdef ATTN_EXP_SKIP_VALU
-      p_out[u >> 2][u & 3] = __float_as_uint(e0[u]) ^ __float_as_uint(e1[u]); return;
-#endif
-      p_out[u >> 2][u & 3] = pack_bf16(e0[u], e1[u]);
-      ls0 += e0[u];
-      ls1 += e1[u];
-    };
+    float ls = exp_block(s_in, p_out);
+    // pipeline: per MFMA one exponential, the plain vector work spread evenly, and the LDS
+    // reads of the operand RA MFMAs ahead (one 128-bit K read or two transposing V reads)
+    constexpr int NVALU = 16 + 14 + 8 + 2;  // multiply-adds, adds, packs, final add + compare
+    step_pipeline<0, NM, RA, NVALU>();
+    if (__builtin_amdgcn_ballot_w64(!(ls <= kSumLimit)) != 0) {
+      float mx = fmaxf(s_in[0], s_in[1]);
 #pragma unroll
-    for (int m = 0; m < NOPS; ++m) {
-      if (m % 3 == 0) {
-        s_out = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, opnd[m]), qf[NQA + m / 3], s_out, 0, 0, 0);
-      } else {
-        const int i = (m / 3) * 2 + (m % 3 - 1);
-        const int cb = i % NCB, kc = i / NCB;
-        oacc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, opnd[m]), __builtin_bit_cast(bf16x8, p_pv[kc]),
-                                                           oacc[cb], 0, 0, 0);
-      }
-      if (m + RA < NOPS) read_op(m + RA);
-      if (m >= NOPS - NQA - 2 && m < NOPS - 2) ka[m - (NOPS - NQA - 2)] = k_operand(knext, m - (NOPS - NQA - 2));
-      // the 8 exponential units (2 elements each) are spread evenly over the NOPS MFMAs
+      for (int r = 2; r < 16; ++r) mx = fmaxf(mx, s_in[r]);
+      mx = attn_max_halves(mx) * c;
+      const float m_new = fmaxf(m_ref, mx);
+      const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);  // exp2(-inf) = 0 on the first block
+      m_ref = m_new;
+      l_run *= alpha;
 #pragma unroll
-      for (int u = 0; u < 8; ++u)
-        if (u * NOPS / 8 == m) {
-          unit_front(u);
-          if (u > 0) unit_back(u - 1);
-        }
-      __builtin_amdgcn_sched_barrier(0);
+      for (int cb = 0; cb < NCB; ++cb) oacc[cb] *= alpha;
+      ls = exp_block(s_in, p_out);
     }
-    unit_back(7);
-    l_run += ls0 + ls1;
+    l_run += ls;
   };
 
   // the same step for blocks that may be masked or not visible to this wave (run-time offsets)
@@ -390,7 +380,7 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_bf16_sp_kernel(const AttnPara
   else ATTN_WAIT_VMCNT(0);
   attn_wg_barrier();  // bundle 0 is full; the K part of slot 2 is empty again
 #pragma unroll
-  for (int i = 0; i < NQA; ++i) ka[i] = k_operand(0, i);  // part-A operands of the first pipelined step
+  for (int m = 0; m < RA; ++m) pre[m] = step_operand(ic<0>{}, m);  // first operands of the first pipelined step
 
   // ---- main loop over bundles ------------------------------------------------------------------------
   // iteration b: exponentiate blocks 2b+1 and 2b+2, compute the scores of blocks 2b+2 and 2b+3
@@ -407,9 +397,9 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_bf16_sp_kernel(const AttnPara
   };
   auto bundle_hot = [&](int b, auto slot_tag) __attribute__((always_inline)) {
     constexpr int SLOT = decltype(slot_tag)::value;
-    step_hot(s_a, s_b, p_a, p_b, ic<SLOT * TILEB>{}, ic<SLOT * TILEB>{}, ic<SLOT * TILEB + SUBB>{});
+    step_hot(s_a, s_b, p_a, p_b, ic<SLOT * TILEB>{}, ic<SLOT * TILEB + SUBB>{});
     bundle_mid(b, (SLOT + 2) % NSLOT);
-    step_hot(s_b, s_a, p_b, p_a, ic<SLOT * TILEB + SUBB>{}, ic<SLOT * TILEB + SUBB>{}, ic<((SLOT + 1) % NSLOT) * TILEB>{});
+    step_hot(s_b, s_a, p_b, p_a, ic<SLOT * TILEB + SUBB>{}, ic<((SLOT + 1) % NSLOT) * TILEB>{});
   };
   auto bundle_any = [&](int b, int slot) __attribute__((always_inline)) {
     const int k1 = (2 * b + 1) * 32, k2 = k1 + 32;
