@@ -29,7 +29,7 @@ sys.path.insert(0, ROOT)
 PEAK_TFLOPS = {"bf16": 2516.6, "fp8_e4m3": 5033.2}  # 256 CUs x 2.4 GHz x 4096 (8192) flop/clk/CU, dense
 # HBM bytes per launch measured with rocprofv3 (FETCH_SIZE x 2.0 KiB + WRITE_SIZE x 1.0 KiB, factors from
 # a 1 GiB copy); the runs and figures are in profiles/.  None where no such run has been made.
-MEASURED_TRAFFIC_BYTES = {"long_noncausal_8k": 5.392e8}
+MEASURED_TRAFFIC_BYTES = {"long_noncausal_8k": 5.393e8}
 
 
 def log(*a):

@@ -7,10 +7,12 @@
 //
 //  * q_descale * k_descale is folded into the exponent constant, v_descale into the final
 //    normalisation: no extra pass over memory.
-//  * P is stored as e4m3 of 2^6 * exp2(c s - m): with the running maximum allowed to lag a
-//    block maximum by at most 2^2 the stored values stay <= 256 < 448 (the e4m3 conversion
-//    does not saturate: it returns NaN above 464), and values down to 2^-12 keep a normal
-//    encoding.  The factor 2^6 cancels in O = acc / l.
+//  * P is stored as e4m3 of 2^6 * exp2(c s - m).  The exponentials of a tile are taken against
+//    the current reference maximum without looking at the tile's own maximum; the tile is redone
+//    with a raised reference only if a lane's partial row sum exceeds 448 (the e4m3 conversion
+//    does not saturate: it returns NaN above 464; a sum of non-negative terms below 448 bounds
+//    every term).  Values down to 2^-12 keep a normal encoding.  The factor 2^6 cancels in
+//    O = acc / l.
 //  * P enters the second product as the SUM OF TWO e4m3 TERMS: the e4m3 rounding of P and the
 //    e4m3 rounding of what that rounding lost (converted back with v_cvt_pk_f32_fp8 and
 //    subtracted in fp32).  One term alone carries 3 mantissa bits, a relative error of 2.6 %
@@ -38,7 +40,7 @@ namespace {
 typedef __attribute__((ext_vector_type(8))) int i32x8;
 typedef __attribute__((ext_vector_type(2))) int i32x2;
 
-constexpr float kTau = 2.0f;     // the reference maximum may lag a block maximum by 2^2
+constexpr float kSumLimit = 448.0f;  // largest finite e4m3 value: a 32-term partial sum below it bounds every term
 constexpr float kPShift = 6.0f;  // P is stored as 2^6 * exp2(.)
 
 // 16-byte-chunk swizzle of the V tile for the 8-bit transposing load: 16 lanes read 16 bytes
@@ -180,45 +182,53 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_fp8_kernel(const AttnParams p
         for (int r = 0; r < 16; ++r)
           if (kbase + kb * 32 + 8 * (r >> 2) + (r & 3) > limit) s[kb][r] = -INFINITY;
     }
-    // row maximum of the tile and the (rare) rescale
-    float mx = fmaxf(s[0][0], s[1][0]);
+    // P^T = 2^6 exp2(c S^T - m) as two e4m3 terms, packed four keys to a dword in accumulator
+    // order.  Optimistic pass against the current reference maximum; if a lane's partial row
+    // sum exceeds the largest e4m3 value (only then could a term leave the e4m3 range) or is
+    // not a number (first tile), the true tile maximum is taken, the reference raised, the
+    // accumulator rescaled and the tile redone.
+    i32x8 phi, plo;
+    auto exp_tile = [&]() __attribute__((always_inline)) {
+      const float msub = m_ref - kPShift;
+      float ls0 = 0.f, ls1 = 0.f;
 #pragma unroll
-    for (int r = 1; r < 16; ++r) mx = fmaxf(mx, fmaxf(s[0][r], s[1][r]));
-    mx = attn_max_halves(mx) * c;
-    if (__builtin_amdgcn_ballot_w64(mx > m_ref + kTau) != 0) {
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+          const float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][4 * b + 0], c, -msub));
+          const float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][4 * b + 1], c, -msub));
+          const float e2 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][4 * b + 2], c, -msub));
+          const float e3 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][4 * b + 3], c, -msub));
+          int hi = 0;
+          hi = __builtin_amdgcn_cvt_pk_fp8_f32(e0, e1, hi, false);
+          hi = __builtin_amdgcn_cvt_pk_fp8_f32(e2, e3, hi, true);
+          const auto b01 = __builtin_amdgcn_cvt_pk_f32_fp8(hi, false);
+          const auto b23 = __builtin_amdgcn_cvt_pk_f32_fp8(hi, true);
+          int lo = 0;
+          lo = __builtin_amdgcn_cvt_pk_fp8_f32(e0 - b01[0], e1 - b01[1], lo, false);
+          lo = __builtin_amdgcn_cvt_pk_fp8_f32(e2 - b23[0], e3 - b23[1], lo, true);
+          phi[kb * 4 + b] = hi;
+          plo[kb * 4 + b] = lo;
+          ls0 += e0 + e2;
+          ls1 += e1 + e3;
+        }
+      return ls0 + ls1;
+    };
+    float ls = exp_tile();
+    if (__builtin_amdgcn_ballot_w64(!(ls <= kSumLimit)) != 0) {
+      float mx = fmaxf(s[0][0], s[1][0]);
+#pragma unroll
+      for (int r = 1; r < 16; ++r) mx = fmaxf(mx, fmaxf(s[0][r], s[1][r]));
+      mx = attn_max_halves(mx) * c;
       const float m_new = fmaxf(m_ref, mx);
       const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);
       m_ref = m_new;
       l_run *= alpha;
 #pragma unroll
       for (int cb = 0; cb < NCB; ++cb) oacc[cb] *= alpha;
+      ls = exp_tile();
     }
-    // P^T = 2^6 exp2(c S^T - m) as two e4m3 terms, packed four keys to a dword in accumulator order
-    const float msub = m_ref - kPShift;
-    i32x8 phi, plo;
-    float ls0 = 0.f, ls1 = 0.f;
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int b = 0; b < 4; ++b) {
-        const float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][4 * b + 0], c, -msub));
-        const float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][4 * b + 1], c, -msub));
-        const float e2 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][4 * b + 2], c, -msub));
-        const float e3 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][4 * b + 3], c, -msub));
-        int hi = 0;
-        hi = __builtin_amdgcn_cvt_pk_fp8_f32(e0, e1, hi, false);
-        hi = __builtin_amdgcn_cvt_pk_fp8_f32(e2, e3, hi, true);
-        const auto b01 = __builtin_amdgcn_cvt_pk_f32_fp8(hi, false);
-        const auto b23 = __builtin_amdgcn_cvt_pk_f32_fp8(hi, true);
-        int lo = 0;
-        lo = __builtin_amdgcn_cvt_pk_fp8_f32(e0 - b01[0], e1 - b01[1], lo, false);
-        lo = __builtin_amdgcn_cvt_pk_fp8_f32(e2 - b23[0], e3 - b23[1], lo, true);
-        phi[kb * 4 + b] = hi;
-        plo[kb * 4 + b] = lo;
-        ls0 += e0 + e2;
-        ls1 += e1 + e3;
-      }
-    l_run += ls0 + ls1;
+    l_run += ls;
     // O^T += V^T (P_hi + P_lo)^T
 #pragma unroll
     for (int cb = 0; cb < NCB; ++cb) {

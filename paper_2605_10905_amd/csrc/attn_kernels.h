@@ -32,3 +32,4 @@ const AttnVariant* attn_bf16_variants(int* count);
 const AttnVariant* attn_bf16_pp_variants(int* count);
 const AttnVariant* attn_bf16_sp_variants(int* count);
 const AttnVariant* attn_fp8_variants(int* count);
+const AttnVariant* attn_fp8_sp_variants(int* count);
