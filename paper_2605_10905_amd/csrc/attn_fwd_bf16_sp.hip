@@ -77,7 +77,10 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_bf16_sp_kernel(const AttnPara
   constexpr int NCH = ROWB / 16;    // 16-byte chunks per row
   constexpr int TILEB = BN * ROWB;  // bytes per K (or V) tile
   constexpr int SUBB = 32 * ROWB;   // bytes per 32-key block
-  constexpr int NSLOT = 3;
+#ifndef ATTN_SP_NSLOT
+#define ATTN_SP_NSLOT 3
+#endif
+  constexpr int NSLOT = ATTN_SP_NSLOT;  // ring depth: bundles are requested NSLOT-1 ahead
   constexpr int VBASE = NSLOT * TILEB;  // K parts of the slots first, then the V parts
   constexpr int NLD = BN * NCH / NT;    // direct-to-LDS loads per thread per tile
 #ifndef ATTN_RA
@@ -86,7 +89,7 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_bf16_sp_kernel(const AttnPara
   constexpr int RA = ATTN_RA;           // operands are read from LDS this many MFMAs ahead
   static_assert(BN * NCH % NT == 0 && NLD >= 1, "tile must divide evenly over the workgroup");
   static_assert(NKK == 2 * NCB && RA >= 2 && RA <= 2 * NKK, "one PV step per QK^T step; read-ahead within a step");
-  static_assert(NSLOT * TILEB < 65536, "ring offsets must fit the 16-bit LDS immediate");
+  static_assert((NSLOT - 1) * TILEB + SUBB + 16 * ROWB < 65536 && (NSLOT == 3 || NSLOT == 4), "ring offsets must fit the 16-bit LDS immediate");
 
   __shared__ __attribute__((aligned(1024))) char smem_raw[2 * NSLOT * TILEB];
   LDS_AS char* const smem = (LDS_AS char*)smem_raw;
@@ -146,7 +149,7 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_bf16_sp_kernel(const AttnPara
     issue_tile(vhead, b, ld_voff, lds_wave + VBASE + slot * TILEB);
   };
 
-  issue_tile(khead, 0, ld_koff, lds_wave + 2 * TILEB);  // key tile 0 borrows the K part of slot 2
+  issue_tile(khead, 0, ld_koff, lds_wave + (NSLOT - 1) * TILEB);  // key tile 0 borrows the K part of the last slot
   issue_bundle(0, 0);
 
   // ---- Q operand (B operand of S^T = K Q^T): lane (qi,h) holds Q[row][16kk+8h .. +7] ----------
@@ -158,6 +161,7 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_bf16_sp_kernel(const AttnPara
     for (int kk = 0; kk < NKK; ++kk) qf[kk] = *(const bf16x8*)(src + kk * 32);
   }
   if (nt > 1) issue_bundle(1, 1);
+  if (NSLOT > 3 && nt > 2) issue_bundle(2, 2);
 
   // ---- LDS read addresses (slot 0, first 32-key block) -----------------------------------------
   uint32_t kaddr[NKK];
@@ -366,19 +370,21 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_bf16_sp_kernel(const AttnPara
 
   // ---- prologue: block 0 ---------------------------------------------------------------------------
   // key tile 0 (and Q) have landed once only the bundle loads issued after them are outstanding
-  if (nt > 1) ATTN_WAIT_VMCNT(4 * NLD);
+  if (NSLOT > 3 && nt > 2) ATTN_WAIT_VMCNT(6 * NLD);
+  else if (nt > 1) ATTN_WAIT_VMCNT(4 * NLD);
   else ATTN_WAIT_VMCNT(2 * NLD);
 #pragma unroll
   for (int kk = 0; kk < NKK; ++kk) asm volatile("" ::"v"(qf[kk]));  // Q is in registers from here on
   attn_wg_barrier();
   if (wave_valid) {
-    qk_block(s_b, 2 * TILEB);                          // S(0)
+    qk_block(s_b, (NSLOT - 1) * TILEB);                          // S(0)
     softmax_block(s_b, p_b, p_a, 0, needs_mask(0));    // P(0) -> p_b (nothing pending yet)
-    qk_block(s_a, 2 * TILEB + SUBB);                   // S(1); ignored if block 1 is not visible
+    qk_block(s_a, (NSLOT - 1) * TILEB + SUBB);                   // S(1); ignored if block 1 is not visible
   }
-  if (nt > 1) ATTN_WAIT_VMCNT(2 * NLD);
+  if (NSLOT > 3 && nt > 2) ATTN_WAIT_VMCNT(4 * NLD);
+  else if (nt > 1) ATTN_WAIT_VMCNT(2 * NLD);
   else ATTN_WAIT_VMCNT(0);
-  attn_wg_barrier();  // bundle 0 is full; the K part of slot 2 is empty again
+  attn_wg_barrier();  // bundle 0 is full; the K part of the last slot is empty again
 #pragma unroll
   for (int m = 0; m < RA; ++m) pre[m] = step_operand(ic<0>{}, m);  // first operands of the first pipelined step
 
@@ -389,16 +395,17 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_bf16_sp_kernel(const AttnPara
   // loads in flight) is published, and the slot of bundle b-1, which every wave has finished
   // reading, is handed to bundle b+2
   auto bundle_mid = [&](int b, int free_slot) __attribute__((always_inline)) {
-    ATTN_WAIT_VMCNT(0);
+    if (NSLOT > 3 && b + 2 < nt) ATTN_WAIT_VMCNT(2 * NLD);  // bundle b+2 may stay in flight
+    else ATTN_WAIT_VMCNT(0);
 #ifndef ATTN_EXP_NOBAR
     attn_wg_barrier();
 #endif
-    if (b + 2 < nt) issue_bundle(b + 2, free_slot);
+    if (b + NSLOT - 1 < nt) issue_bundle(b + NSLOT - 1, free_slot);
   };
   auto bundle_hot = [&](int b, auto slot_tag) __attribute__((always_inline)) {
     constexpr int SLOT = decltype(slot_tag)::value;
     step_hot(s_a, s_b, p_a, p_b, ic<SLOT * TILEB>{}, ic<SLOT * TILEB + SUBB>{});
-    bundle_mid(b, (SLOT + 2) % NSLOT);
+    bundle_mid(b, (SLOT + NSLOT - 1) % NSLOT);
     step_hot(s_b, s_a, p_b, p_a, ic<SLOT * TILEB + SUBB>{}, ic<((SLOT + 1) % NSLOT) * TILEB>{});
   };
   auto bundle_any = [&](int b, int slot) __attribute__((always_inline)) {
@@ -417,6 +424,7 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_bf16_sp_kernel(const AttnPara
     bundle_hot(b, ic<0>{});
     bundle_hot(b + 1, ic<1>{});
     bundle_hot(b + 2, ic<2>{});
+    if (NSLOT > 3) bundle_hot(b + 3, ic<3 % NSLOT>{});
   }
   for (int slot = 0; b < nt; ++b) {  // b is a multiple of NSLOT here, so the ring is at slot 0
     bundle_any(b, slot);

@@ -31,5 +31,6 @@ struct AttnVariant {
 const AttnVariant* attn_bf16_variants(int* count);
 const AttnVariant* attn_bf16_pp_variants(int* count);
 const AttnVariant* attn_bf16_sp_variants(int* count);
+const AttnVariant* attn_bf16_w16_variants(int* count);
 const AttnVariant* attn_fp8_variants(int* count);
 const AttnVariant* attn_fp8_sp_variants(int* count);
