@@ -432,16 +432,21 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_bf16_w16_kernel(const AttnPar
 
   // bundles 0 .. n_hot-1 touch only blocks (up to 2b+2) that every query of this wave sees in full
   const int vis = CAUSAL ? min(wq0, N - 1) : N - 1;  // last key every query of the wave can see
-  int n_hot = (wave_valid && vis >= 95) ? (vis - 95) / 64 + 1 : 0;
-  n_hot -= n_hot % NSLOT;
+  const int n_hot = (wave_valid && vis >= 95) ? (vis - 95) / 64 + 1 : 0;
+  const int n_ring = n_hot - n_hot % NSLOT;  // whole turns of the ring, slot offsets as immediates
   int b = 0;
-  for (; b < n_hot; b += NSLOT) {
+  for (; b < n_ring; b += NSLOT) {
     bundle_hot(b, ic<0>{});
     bundle_hot(b + 1, ic<1>{});
     bundle_hot(b + 2, ic<2>{});
     if (NSLOT > 3) bundle_hot(b + 3, ic<3 % NSLOT>{});
   }
-  for (int slot = 0; b < nt; ++b) {  // b is a multiple of NSLOT here, so the ring is at slot 0
+  // the last fully visible bundles (fewer than a turn), then the masked / partly visible ones
+  int slot = 0;
+  if (b < n_hot) { bundle_hot(b, ic<0>{}); ++b; slot = 1; }
+  if (b < n_hot) { bundle_hot(b, ic<1>{}); ++b; slot = 2; }
+  if (NSLOT > 3 && b < n_hot) { bundle_hot(b, ic<2>{}); ++b; slot = 3 % NSLOT; }
+  for (; b < nt; ++b) {
     bundle_any(b, slot);
     slot = slot == NSLOT - 1 ? 0 : slot + 1;
   }

@@ -43,11 +43,13 @@ typedef __attribute__((ext_vector_type(2))) int i32x2;
 constexpr float kSumLimit = 448.0f;  // largest finite e4m3 value: a 32-term partial sum below it bounds every term
 constexpr float kPShift = 6.0f;  // P is stored as 2^6 * exp2(.)
 
-// 16-byte-chunk swizzle of the V tile for the 8-bit transposing load: 16 lanes read 16 bytes
-// of each of the rows r, r+1, r+2, r+3, r+8, .., r+11 (r a multiple of 4); with 128-byte rows
-// two consecutive rows already sit in different halves of the 64 banks, bits 1 and 3 of the
-// row pick one of four 16-byte groups.
-__device__ __forceinline__ constexpr int swz_v8(int row) { return ((row >> 1) & 1) | (((row >> 3) & 1) << 1); }
+// 16-byte-chunk swizzle of the V tile for the 8-bit transposing load.  A 16-lane group reads
+// 16 bytes of each of the rows r .. r+3 and r+8 .. r+11 (r a multiple of 4) and two groups
+// that read neighbouring chunks of the same rows are served together.  With 128-byte rows two
+// consecutive rows already sit in different halves of the 64 banks; bits 1 and 3 of the row
+// move the chunk PAIR, so the four rows of a bank half and the two chunks of a pair cover all
+// eight 16-byte groups of that half.
+__device__ __forceinline__ constexpr int swz_v8(int row) { return (((row >> 1) & 1) | (((row >> 3) & 1) << 1)) << 1; }
 
 template <int D, bool CAUSAL>
 __global__ void __launch_bounds__(512, 2) attn_fwd_fp8_kernel(const AttnParams p) {
