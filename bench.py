@@ -7,8 +7,10 @@ quoted on: B=2, Hq=Hkv=32, N=8192, d=128, bf16, non-causal, synthetic N(0,1)*0.5
 inputs already resident in HBM.  Prints ONE JSON line on stdout.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--config I] [--variant V]
-                  [--no-cpu-baseline] [--all-configs] [--copy-calibration]
+                  [--no-cpu-baseline] [--all-configs] [--paper-grid] [--copy-calibration]
 
+--paper-grid also times the paper's own attention shape grid (appendix A: batch 4, 48 heads,
+N = 1024 .. 16384, d = 128, causal and non-causal) and reports it under 'paper_grid'.
 --copy-calibration runs nothing but a 1 GiB device-to-device copy (three times): under
 `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE` it gives the factor that converts those
 counters into bytes (see profiles/).
@@ -78,6 +80,45 @@ def time_config(A, torch, cfg, steps, warmup, variant=None):
                 kern_ms_med=float(np.median(kern_ms)), flops=flops)
 
 
+def time_paper_grid(A, torch):
+    """The paper's attention benchmark grid, bf16.  Inputs are drawn on the device (seeded
+    N(0,1), rounded to bf16): only their statistics matter for timing; parity on these shapes
+    is covered by the tests."""
+    import workloads as wl
+
+    rows = []
+    gen = torch.Generator(device="cuda")
+    for cfg in wl.paper_grid():
+        B, H, N, d = cfg["B"], cfg["Hq"], cfg["N"], cfg["d"]
+        gen.manual_seed(cfg["seed"])
+        q, k, v = (torch.randn((B, H, N, d), device="cuda", generator=gen).to(torch.bfloat16) for _ in range(3))
+        o = torch.empty_like(q)
+        lse = torch.empty((B, H, N), dtype=torch.float32, device="cuda")
+        stream = torch.cuda.current_stream()
+
+        def step():
+            A.attn_fwd(q, k, v, o, lse, B, H, H, N, d, cfg["causal"], cfg["scale"], A.ATTN_BF16, stream=stream)
+
+        flops = wl.algorithmic_flops(cfg)
+        est = flops / 1.0e15
+        for _ in range(max(3, min(200, int(0.05 / est)))):
+            step()
+        torch.cuda.synchronize()
+        n = max(5, min(50, int(0.05 / est)))
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+        for a, b in evs:
+            a.record(stream)
+            step()
+            b.record(stream)
+        torch.cuda.synchronize()
+        ms = float(np.median([a.elapsed_time(b) for a, b in evs]))
+        tf = flops / (ms * 1e-3) / 1e12
+        rows.append({"workload": cfg["name"], "kernel_ms": ms, "TFLOP/s": tf, "pct_of_dense_peak": 100 * tf / PEAK_TFLOPS["bf16"]})
+        log(f"[bench] {cfg['name']}: {ms:.4f} ms  {tf:.1f} TFLOP/s = {100 * tf / PEAK_TFLOPS['bf16']:.1f}%")
+        del q, k, v, o, lse
+    return rows
+
+
 def cpu_baseline(cfg, inp, budget_s=20.0):
     """The oracle as it stands, timed on the host cores on a bounded sample: whole
     (b, h) heads of the same workload, one after another, until the time budget is
@@ -126,6 +167,7 @@ def main():
     ap.add_argument("--variant", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--all-configs", action="store_true", help="also time the other bf16 configs (reported in 'others')")
+    ap.add_argument("--paper-grid", action="store_true", help="also time the paper's attention shape grid (reported in 'paper_grid')")
     ap.add_argument("--copy-calibration", action="store_true", help="only run a 1 GiB copy (counter calibration)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -192,6 +234,8 @@ def main():
             log(f"[bench] {c['name']}: {rr['kern_ms_med']:.4f} ms  {tf:.1f} TFLOP/s")
             del rr
         out["others"] = others
+    if args.paper_grid:
+        out["paper_grid"] = time_paper_grid(A, torch)
     if not args.no_cpu_baseline:
         log("[bench] timing the CPU oracle on a bounded sample ...")
         out["cpu_baseline"] = cpu_baseline(cfg, r["inp"])

@@ -192,3 +192,25 @@ def test_full_size_sampled(ci):
         lo = vcol.min(dim=0, keepdim=True).values
     eps = 1e-2 * (hi - lo).abs() + 2.0 ** -8 * oo.abs() + 1e-6  # slack: bf16 rounding of the output
     assert bool(((oo <= hi + eps) & (oo >= lo - eps)).all())
+
+
+# ---- the paper's own shape grid (d = 128; one batch element; all 48 heads at N = 1024, 8 heads
+# at the longer lengths so that drawing the inputs on the host stays within seconds) ------------
+@pytest.mark.parametrize("N,causal", [(1024, True), (1024, False), (4096, True), (16384, True), (16384, False)])
+def test_paper_grid_shapes_sampled(N, causal):
+    cfg = next(c for c in wl.paper_grid() if c["N"] == N and c["causal"] == causal)
+    print(f"paper grid N={N} causal={causal}: generating inputs", flush=True)
+    H = 48 if N <= 1024 else 8
+    inp = wl.make_inputs(cfg, B=1, Hq=H, Hkv=H)
+    dev = gu.to_device(inp)
+    print(f"paper grid N={N} causal={causal}: launching", flush=True)
+    o, lse = gu.run_gpu(inp, dev)
+    assert torch.isfinite(o.float()).all() and torch.isfinite(lse).all()
+    rng = np.random.default_rng(300 + N + int(causal))
+    heads = [(0, 0), (0, H - 1), (0, int(rng.integers(0, H)))]
+    rows = [gu.sample_rows(N, 256, rng, n_random=16) for _ in heads]
+    m = gu.check_sampled(inp, o, lse, heads, rows, f"paper grid N={N} causal={causal}")
+    print(f"paper grid N={N} causal={causal}: {m}", flush=True)
+    if N <= 4096:
+        mh = gu.check_whole_head(inp, o, lse, 0, heads[2][1], f"paper grid N={N} causal={causal}, whole head")
+        print(f"paper grid N={N} causal={causal}: whole head {mh}", flush=True)
