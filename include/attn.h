@@ -79,6 +79,32 @@ int attn_fwd_fp8(const void* q, const void* k, const void* v, void* o, float* ls
                  float q_descale, float k_descale, float v_descale, void* stream);
 
 /*
+ * attn_bwd -- attention backward (the paper lists the backward pass beside the forward among
+ * its attention kernels, section 6.1; appendix A, attention shape table, backward rows).
+ * Gradients of attn_fwd with respect to q, k and v, given the gradient `dout` of o:
+ *
+ *     P = exp(S - lse) ;  dV = P^T dO ;  dP = dO V^T ;  dS = P * (dP - rowsum(dO * O))
+ *     dQ = scale dS K ;  dK = scale dS^T Q      (dK, dV summed over the query heads of a group)
+ *
+ *   q,k,v,o,lse   the forward call's inputs and outputs (device; layouts as for attn_fwd)
+ *   dout          device, bfloat16 [B,Hq,N,d]
+ *   dq            device, bfloat16 [B,Hq,N,d], overwritten
+ *   dk,dv         device, bfloat16 [B,Hkv,N,d], overwritten
+ *   workspace     device, attn_bwd_workspace_bytes(B,Hq,N) bytes, 16-byte aligned, owned by the
+ *                 caller; contents on entry are irrelevant, contents on return unspecified
+ *   dtype         ATTN_BF16 only; d must be 128 (ATTN_ERR_UNSUPPORTED otherwise)
+ *
+ * Deterministic (no atomics).  Three kernels are enqueued on `stream`; the call returns without
+ * synchronising.  Returns an attn_status; argument checks run before anything is enqueued.
+ */
+int attn_bwd(const void* q, const void* k, const void* v, const void* o, const void* dout, const float* lse,
+             void* dq, void* dk, void* dv, float* workspace,
+             int B, int Hq, int Hkv, int N, int d, int causal, float scale, int dtype, void* stream);
+
+/* Size in bytes of the workspace attn_bwd needs (0 for non-positive sizes). */
+long long attn_bwd_workspace_bytes(int B, int Hq, int N);
+
+/*
  * attn_fwd_variant -- tuning hook: as attn_fwd, but with the kernel variant
  * forced (see attn_variant_name) instead of chosen by the library.  Returns
  * ATTN_ERR_UNSUPPORTED if the variant does not exist for this d / dtype.

@@ -34,6 +34,10 @@ lib.attn_fwd_fp8.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _f
 lib.attn_fwd_fp8.restype = _i
 lib.attn_fwd_variant.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _f, _i, _i, _vp]
 lib.attn_fwd_variant.restype = _i
+lib.attn_bwd.argtypes = [_vp] * 10 + [_i, _i, _i, _i, _i, _i, _f, _i, _vp]
+lib.attn_bwd.restype = _i
+lib.attn_bwd_workspace_bytes.argtypes = [_i, _i, _i]
+lib.attn_bwd_workspace_bytes.restype = C.c_longlong
 lib.attn_num_variants.argtypes = []
 lib.attn_num_variants.restype = _i
 lib.attn_variant_name.argtypes = [_i]
@@ -124,4 +128,17 @@ def attn_fwd_variant(q, k, v, o, lse, B, Hq, Hkv, N, d, causal, scale, dtype, va
                               float(scale), int(dtype), int(variant), _stream(stream))
     if check and st != 0:
         raise AttnError(st, "attn_fwd_variant")
+    return st
+
+
+def attn_bwd_workspace_bytes(B: int, Hq: int, N: int) -> int:
+    return lib.attn_bwd_workspace_bytes(B, Hq, N)
+
+
+def attn_bwd(q, k, v, o, dout, lse, dq, dk, dv, workspace, B, Hq, Hkv, N, d, causal, scale, dtype, stream=None,
+             check=True):
+    st = lib.attn_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(dout), _ptr(lse), _ptr(dq), _ptr(dk), _ptr(dv),
+                      _ptr(workspace), B, Hq, Hkv, N, d, int(bool(causal)), float(scale), int(dtype), _stream(stream))
+    if check and st != 0:
+        raise AttnError(st, "attn_bwd")
     return st

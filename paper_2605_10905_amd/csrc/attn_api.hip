@@ -121,6 +121,36 @@ int attn_fwd_variant(const void* q, const void* k, const void* v, void* o, float
   return run(q, k, v, o, lse, B, Hq, Hkv, N, d, causal, scale, dtype, 1.0f, 1.0f, variant, stream);
 }
 
+int attn_bwd(const void* q, const void* k, const void* v, const void* o, const void* dout, const float* lse, void* dq, void* dk,
+             void* dv, float* workspace, int B, int Hq, int Hkv, int N, int d, int causal, float scale, int dtype, void* stream) {
+  if (!q || !k || !v || !o || !dout || !lse || !dq || !dk || !dv || !workspace) return ATTN_ERR_NULL;
+  if (dtype != ATTN_BF16 && dtype != ATTN_FP8_E4M3) return ATTN_ERR_DTYPE;
+  if (B <= 0 || Hq <= 0 || Hkv <= 0 || N <= 0 || d <= 0 || Hq % Hkv != 0) return ATTN_ERR_SHAPE;
+  const void* const ptrs[] = {q, k, v, o, dout, dq, dk, dv, workspace};
+  for (const void* ptr : ptrs)
+    if (misaligned(ptr, 16)) return ATTN_ERR_SHAPE;
+  if (misaligned(lse, 4)) return ATTN_ERR_SHAPE;
+  if (dtype != ATTN_BF16 || d != 128) return ATTN_ERR_UNSUPPORTED;
+  if (scale <= 0.0f) return ATTN_ERR_UNSUPPORTED;
+  if ((long long)N * d * 2 >= (1ll << 31)) return ATTN_ERR_UNSUPPORTED;
+  AttnBwdParams p;
+  p.q = q; p.k = k; p.v = v; p.o = o; p.dout = dout; p.lse = lse;
+  p.dq = dq; p.dk = dk; p.dv = dv; p.ws = workspace;
+  p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.N = N;
+  p.T = (N + 255) / 256;
+  p.Npad = (N + 63) / 64 * 64;
+  p.causal = causal ? 1 : 0;
+  p.scale_log2 = scale * kLog2e;
+  p.scale = scale;
+  if ((long long)B * Hq * p.T > 0x7fffffffll) return ATTN_ERR_UNSUPPORTED;
+  return attn_bwd_launch_bf16_d128(p, (hipStream_t)stream) == 0 ? ATTN_OK : ATTN_ERR_LAUNCH;
+}
+
+long long attn_bwd_workspace_bytes(int B, int Hq, int N) {
+  if (B <= 0 || Hq <= 0 || N <= 0) return 0;
+  return (long long)B * Hq * 2 * ((N + 63) / 64 * 64) * (long long)sizeof(float);
+}
+
 int attn_num_variants(void) { return total_variants(); }
 
 const char* attn_variant_name(int variant) {

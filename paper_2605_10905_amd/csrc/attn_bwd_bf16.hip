@@ -1,0 +1,462 @@
+// Attention backward, bf16, gfx950 (head dimension 128).
+//
+// The paper lists the backward pass beside the forward among its attention kernels (section
+// 6.1; appendix A, attention shape table, backward rows).  Given Q, K, V, the forward output O
+// with its per-row logsumexp, and the output gradient dO:
+//
+//     P  = exp(scale Q K^T - lse)             (rebuilt from the stored statistic, no maximum needed)
+//     dV = P^T dO        dP = dO V^T        delta_i = sum_d dO_id O_id
+//     dS = P * (dP - delta)                 dQ = scale dS K        dK = scale dS^T Q
+//
+// Three kernels, none of which uses atomics or a reduction across workgroups, so the result is
+// deterministic and dQ needs no fp32 accumulation buffer in memory:
+//
+//   * attn_bwd_dq_kernel: a workgroup owns 256 query rows (Q and dO rows stationary in registers
+//     as MFMA B operands, one query per lane, exactly the forward layout) and streams K/V tiles:
+//     S^T = K Q^T, dP^T = V dO^T, dS^T in registers, dQ^T += K^T dS^T.  It also writes the two
+//     per-row vectors the other kernels need, delta and lse * log2(e), into the workspace.
+//   * attn_bwd_dkv_kernel<.., 0>: a workgroup owns 256 keys (K rows stationary, one key per lane)
+//     and streams Q/dO tiles of every query head of its group: S = Q K^T, P, dV^T += dO^T P.
+//   * attn_bwd_dkv_kernel<.., 1>: the same with V rows stationary as well: dP = dO V^T,
+//     dS = P * (dP - delta), dK^T += Q^T dS.
+//   S (and dP) are therefore computed three (two) times, 8 matrix products per tile pair instead
+//   of the minimal 5: the price of keeping every accumulator in registers without atomics.
+//
+// All three share the forward kernels' machinery: 64-row tiles streamed HBM/L2 -> LDS by
+// direct-to-LDS loads into a three-slot ring two tiles ahead (one workgroup barrier per tile),
+// transposed products on the 32x32x16 MFMA so that the exponentiated accumulator is the next
+// B operand in place, and the transposing LDS read for the operand that must be contracted
+// over its row index.  Streamed tiles are read both row-wise and transposed, so their 16-byte
+// chunks are swizzled with a bit-swap of the row (conflict-free for both patterns).
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "attn_device.h"
+#include "attn_kernels.h"
+#include "tile_map.h"
+
+namespace {
+
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+constexpr float kLog2e = 1.4426950408889634f;
+
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+  bf16x2 t;
+  t[0] = (__bf16)a;
+  t[1] = (__bf16)b;
+  return __builtin_bit_cast(uint32_t, t);
+}
+
+// Chunk swizzle of a streamed tile with 256-byte rows (16 chunks): XOR with the bit-swapped
+// low four row bits.  Row-wise operand reads (16 lanes, one chunk of 16 consecutive rows) see
+// 16 different values; transposing reads (16 lanes over 4 consecutive rows x 32 bytes, two
+// such groups on neighbouring chunk pairs served together) see the rows in different
+// 64-byte groups.
+__device__ __forceinline__ constexpr int swz_rt(int row) { return ((row & 3) << 2) | ((row >> 2) & 3); }
+
+struct BwdCommon {
+  static constexpr int D = 128, BN = 64, NWAVES = 8, BM = NWAVES * 32, NT = NWAVES * 64;
+  static constexpr int NKK = D / 16, NCB = D / 32, ROWB = D * 2, NCH = ROWB / 16;
+  static constexpr int TILEB = BN * ROWB, SUBB = 32 * ROWB, NSLOT = 3;
+  static constexpr int T2BASE = NSLOT * TILEB;       // second streamed tensor's slots
+  static constexpr int AUXBASE = 2 * NSLOT * TILEB;  // per-slot 512 bytes: lse*log2e and delta of the tile's 64 rows
+  static constexpr int NLD = BN * NCH / NT;
+  static constexpr int LDS_BYTES = AUXBASE + NSLOT * 512;
+};
+
+// store a transposed accumulator (lane (ci,h) holds rows 32cb + 8a + 4h + r of column ci) as
+// row `row` of a [.., D] bf16 matrix, scaled; the two lane halves exchange so that every lane
+// writes 8 consecutive columns with one 16-byte store
+template <int NCB>
+__device__ __forceinline__ void store_transposed(const f32x16 (&acc)[NCB], float mul, char* rowptr, int h, bool valid) {
+#pragma unroll
+  for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+    for (int a = 0; a < 2; ++a) {
+      uint32_t x[2], y[2];
+#pragma unroll
+      for (int r = 0; r < 2; ++r) {
+        const uint32_t tx = pack_bf16(acc[cb][(2 * a) * 4 + 2 * r] * mul, acc[cb][(2 * a) * 4 + 2 * r + 1] * mul);
+        const uint32_t ty = pack_bf16(acc[cb][(2 * a + 1) * 4 + 2 * r] * mul, acc[cb][(2 * a + 1) * 4 + 2 * r + 1] * mul);
+        auto sw = __builtin_amdgcn_permlane32_swap(tx, ty, false, false);
+        x[r] = sw[0];
+        y[r] = sw[1];
+      }
+      if (valid) {
+        u32x4 out = {x[0], x[1], y[0], y[1]};
+        *(u32x4*)(rowptr + (cb * 32 + a * 16 + h * 8) * 2) = out;
+      }
+    }
+}
+
+// =====================================================================================================
+// dQ (and the workspace vectors)
+// =====================================================================================================
+template <bool CAUSAL>
+__global__ void __launch_bounds__(512, 2) attn_bwd_dq_kernel(const AttnBwdParams p) {
+  using C = BwdCommon;
+  constexpr int NKK = C::NKK, NCB = C::NCB, ROWB = C::ROWB, NCH = C::NCH, TILEB = C::TILEB, SUBB = C::SUBB, NSLOT = C::NSLOT;
+  constexpr int NLD = C::NLD, NT = C::NT, BN = C::BN, BM = C::BM;
+
+  __shared__ __attribute__((aligned(1024))) char smem_raw[2 * NSLOT * TILEB];
+  LDS_AS char* const smem = (LDS_AS char*)smem_raw;
+
+  const int tid = threadIdx.x;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+  const int qi = lane & 31, h = lane >> 5;
+
+  const AttnTileCoord tc = attn_tile_coord_impl(blockIdx.x, p.B, p.Hq, p.Hkv, p.T, CAUSAL ? 1 : 0);
+  const int N = p.N;
+  const int hk = tc.hq / (p.Hq / p.Hkv);
+  const int q0 = tc.t * BM;
+  const int wq0 = q0 + w * 32;
+  const bool wave_valid = wq0 < N;
+  const int qrow = wq0 + qi;
+
+  const size_t qoff = ((size_t)(tc.b * p.Hq + tc.hq) * N) * ROWB;
+  const char* const khead = (const char*)p.k + ((size_t)(tc.b * p.Hkv + hk) * N) * ROWB;
+  const char* const vhead = (const char*)p.v + ((size_t)(tc.b * p.Hkv + hk) * N) * ROWB;
+
+  const int kv_end = CAUSAL ? min(N, q0 + BM) : N;
+  const int nt = (kv_end + BN - 1) / BN;
+
+  // ---- producer role ------------------------------------------------------------------------------
+  int ld_row[NLD];
+  uint32_t ld_off[NLD];
+#pragma unroll
+  for (int it = 0; it < NLD; ++it) {
+    const int s = it * NT + tid;
+    const int r = s / NCH, c = s % NCH;
+    ld_row[it] = r;
+    ld_off[it] = r * ROWB + ((c ^ swz_rt(r)) << 4);
+  }
+  const uint32_t lds_wave = (uint32_t)(uintptr_t)smem + w * 1024;
+  auto issue_tile = [&](int j, int slot) __attribute__((always_inline)) {
+    const char* const kb = khead + (size_t)j * TILEB;
+    const char* const vb = vhead + (size_t)j * TILEB;
+#pragma unroll
+    for (int it = 0; it < NLD; ++it) {
+      const uint32_t over = (uint32_t)max(0, j * BN + ld_row[it] - (N - 1)) * ROWB;  // rows past N-1 re-read row N-1
+      attn_lds_dma16(kb, ld_off[it] - over, lds_wave + slot * TILEB + it * NT * 16);
+      attn_lds_dma16(vb, ld_off[it] - over, lds_wave + C::T2BASE + slot * TILEB + it * NT * 16);
+    }
+  };
+  issue_tile(0, 0);
+
+  // ---- stationary operands: Q and dO rows of this lane's query; delta from dO and O ---------------
+  bf16x8 qf[NKK], dof[NKK];
+  float delta;
+  {
+    const int row = min(qrow, N - 1);
+    const char* qs = (const char*)p.q + qoff + (size_t)row * ROWB + h * 16;
+    const char* ds = (const char*)p.dout + qoff + (size_t)row * ROWB + h * 16;
+    const char* os = (const char*)p.o + qoff + (size_t)row * ROWB + h * 16;
+    float acc = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < NKK; ++kk) {
+      qf[kk] = *(const bf16x8*)(qs + kk * 32);
+      dof[kk] = *(const bf16x8*)(ds + kk * 32);
+      const bf16x8 ov = *(const bf16x8*)(os + kk * 32);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc += (float)dof[kk][e] * (float)ov[e];
+    }
+    delta = attn_sum_halves(acc);
+  }
+  const float lse2 = p.lse[(size_t)(tc.b * p.Hq + tc.hq) * N + min(qrow, N - 1)] * kLog2e;
+  // workspace for the key-side kernels, padded to whole 64-row tiles: rows past N get a
+  // statistic of +inf (their probabilities come out as zero) and delta = 0
+  if (h == 0 && qrow < p.Npad) {
+    float* const wsrow = p.ws + (size_t)(tc.b * p.Hq + tc.hq) * 2 * p.Npad;
+    wsrow[qrow] = qrow < N ? lse2 : INFINITY;
+    wsrow[p.Npad + qrow] = qrow < N ? delta : 0.f;
+  }
+  if (nt > 1) issue_tile(1, 1);
+
+  // ---- LDS read addresses (slot 0, first 32-row block) --------------------------------------------
+  uint32_t raddr[NKK];  // row-wise operand: row qi, chunk 2kk + h
+#pragma unroll
+  for (int kk = 0; kk < NKK; ++kk) raddr[kk] = qi * ROWB + (((2 * kk + h) ^ swz_rt(qi)) << 4);
+  uint32_t taddr[NCB][2];  // transposed operand through the transposing load
+  {
+    const int s = lane & 15, chalf = (lane >> 4) & 1;
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+      for (int e = 0; e < 2; ++e) {
+        const int key = 8 * e + 4 * h + (s >> 2);
+        const int chunk = cb * 4 + chalf * 2 + ((s & 3) >> 1);
+        taddr[cb][e] = key * ROWB + ((chunk ^ swz_rt(key)) << 4) + ((s & 1) << 3);
+      }
+  }
+  auto row_operand = [&](int base, int kk) __attribute__((always_inline)) { return *(LDS_AS bf16x8*)(smem + raddr[kk] + base); };
+  auto tr_operand = [&](int base, int cb, int kc) __attribute__((always_inline)) {
+    const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(smem + taddr[cb][0] + base + kc * 16 * ROWB));
+    const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(smem + taddr[cb][1] + base + kc * 16 * ROWB));
+    s16x8 av;
+    av[0] = v0[0]; av[1] = v0[1]; av[2] = v0[2]; av[3] = v0[3];
+    av[4] = v1[0]; av[5] = v1[1]; av[6] = v1[2]; av[7] = v1[3];
+    return __builtin_bit_cast(bf16x8, av);
+  };
+
+  f32x16 acc[NCB];  // dQ^T
+#pragma unroll
+  for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[cb][r] = 0.f;
+  const float c = p.scale_log2;
+  const int limit = CAUSAL ? min(qrow, N - 1) : (N - 1);
+  const int wlast = wq0 + 31;
+
+  // one 32-key block: `base` = byte offset of the block inside the K slots (V: + T2BASE)
+  auto block = [&](int key0, int base) __attribute__((always_inline)) {
+    f32x16 s, dp;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s[r] = dp[r] = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < NKK; ++kk) {
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_operand(base, kk), qf[kk], s, 0, 0, 0);
+      dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_operand(base + C::T2BASE, kk), dof[kk], dp, 0, 0, 0);
+    }
+    const bool need_mask = (CAUSAL && key0 + 31 > wq0) || key0 + 31 >= N;
+    u32x4 dsk[2];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      float e[2];
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        const int r = 2 * u + t;
+        float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c, -lse2));
+        if (need_mask && key0 + 4 * h + 8 * (r >> 2) + (r & 3) > limit) pr = 0.f;
+        e[t] = pr * (dp[r] - delta);
+      }
+      dsk[u >> 2][u & 3] = pack_bf16(e[0], e[1]);
+    }
+#pragma unroll
+    for (int i = 0; i < 2 * NCB; ++i) {
+      const int cb = i % NCB, kc = i / NCB;
+      acc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_operand(base, cb, kc), __builtin_bit_cast(bf16x8, dsk[kc]), acc[cb], 0, 0, 0);
+    }
+  };
+
+  if (nt > 1) ATTN_WAIT_VMCNT(2 * NLD);
+  else ATTN_WAIT_VMCNT(0);
+#pragma unroll
+  for (int kk = 0; kk < NKK; ++kk) asm volatile("" ::"v"(qf[kk]), "v"(dof[kk]));  // stationary operands are in registers
+  attn_wg_barrier();
+
+  int slot = 0;
+  for (int j = 0; j < nt; ++j) {
+    const int pslot = slot == 0 ? NSLOT - 1 : slot - 1;  // slot of tile j+2 = slot of tile j-1
+    if (j + 2 < nt) issue_tile(j + 2, pslot);
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      const int key0 = j * BN + kb * 32;
+      if (wave_valid && key0 < kv_end && (!CAUSAL || key0 <= wlast)) block(key0, slot * TILEB + kb * SUBB);
+    }
+    if (j + 2 < nt) ATTN_WAIT_VMCNT(2 * NLD);  // tile j+1 has landed; the loads of tile j+2 stay in flight
+    else ATTN_WAIT_VMCNT(0);
+    attn_wg_barrier();
+    slot = slot == NSLOT - 1 ? 0 : slot + 1;
+  }
+
+  store_transposed<NCB>(acc, p.scale, (char*)p.dq + qoff + (size_t)min(qrow, N - 1) * ROWB, h, qrow < N);
+}
+
+// =====================================================================================================
+// dV (WHICH = 0) and dK (WHICH = 1)
+// =====================================================================================================
+template <bool CAUSAL, int WHICH>
+__global__ void __launch_bounds__(512, 2) attn_bwd_dkv_kernel(const AttnBwdParams p) {
+  using C = BwdCommon;
+  constexpr int NKK = C::NKK, NCB = C::NCB, ROWB = C::ROWB, NCH = C::NCH, TILEB = C::TILEB, SUBB = C::SUBB, NSLOT = C::NSLOT;
+  constexpr int NLD = C::NLD, NT = C::NT, BN = C::BN, BM = C::BM;
+
+  __shared__ __attribute__((aligned(1024))) char smem_raw[C::LDS_BYTES];
+  LDS_AS char* const smem = (LDS_AS char*)smem_raw;
+
+  const int tid = threadIdx.x;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+  const int ki = lane & 31, h = lane >> 5;
+
+  // one workgroup per (batch, kv head, key tile); all key tiles of a kv head share an XCD (they
+  // stream the same Q / dO); for causal inputs key tile 0 is the heaviest and goes first
+  const AttnTileCoord tc = attn_tile_coord_impl(blockIdx.x, p.B, p.Hkv, p.Hkv, p.T, 0);
+  const int N = p.N;
+  const int G = p.Hq / p.Hkv;
+  const int g = tc.hq;
+  const int k0 = tc.t * BM;
+  const int wk0 = k0 + w * 32;  // first key of this wave
+  const bool wave_valid = wk0 < N;
+  const int krow = wk0 + ki;
+
+  const size_t koff = ((size_t)(tc.b * p.Hkv + g) * N) * ROWB;
+  // streamed range: query tiles qt0 .. nqt_all-1 of each of the G query heads of the group
+  const int nqt_all = (N + BN - 1) / BN;
+  const int qt0 = CAUSAL ? k0 / BN : 0;
+  const int nqt = nqt_all - qt0;
+  const int nt = G * nqt;
+
+  // ---- producer role ------------------------------------------------------------------------------
+  int ld_row[NLD];
+  uint32_t ld_off[NLD];
+#pragma unroll
+  for (int it = 0; it < NLD; ++it) {
+    const int s = it * NT + tid;
+    const int r = s / NCH, c = s % NCH;
+    ld_row[it] = r;
+    ld_off[it] = r * ROWB + ((c ^ swz_rt(r)) << 4);
+  }
+  const uint32_t lds_base = (uint32_t)(uintptr_t)smem;
+  const uint32_t lds_wave = lds_base + w * 1024;
+  auto issue_tile = [&](int j, int slot) __attribute__((always_inline)) {
+    const int hq = g * G + j / nqt, qt = qt0 + j % nqt;
+    const size_t hoff = ((size_t)(tc.b * p.Hq + hq) * N) * ROWB + (size_t)qt * TILEB;
+    const char* const qb = (const char*)p.q + hoff;
+    const char* const db = (const char*)p.dout + hoff;
+#pragma unroll
+    for (int it = 0; it < NLD; ++it) {
+      const uint32_t over = (uint32_t)max(0, qt * BN + ld_row[it] - (N - 1)) * ROWB;  // rows past N-1 re-read row N-1
+      attn_lds_dma16(qb, ld_off[it] - over, lds_wave + slot * TILEB + it * NT * 16);
+      attn_lds_dma16(db, ld_off[it] - over, lds_wave + C::T2BASE + slot * TILEB + it * NT * 16);
+    }
+    // the tile's 64 statistics and 64 deltas: 32 lanes x 16 bytes, the same for every wave
+    const float* const wsrow = p.ws + (size_t)(tc.b * p.Hq + hq) * 2 * p.Npad + (size_t)qt * BN;
+    const uint32_t aoff = (uint32_t)(((lane & 15) * 4 + ((lane >> 4) & 1) * p.Npad) * 4);
+    if (lane < 32) attn_lds_dma16(wsrow, aoff, lds_base + C::AUXBASE + slot * 512);
+  };
+  issue_tile(0, 0);
+
+  // ---- stationary operands: K (and V) rows of this lane's key ----------------------------------------
+  bf16x8 kf[NKK], vf[WHICH ? NKK : 1];
+  {
+    const int row = min(krow, N - 1);
+    const char* ks = (const char*)p.k + koff + (size_t)row * ROWB + h * 16;
+    const char* vs = (const char*)p.v + koff + (size_t)row * ROWB + h * 16;
+#pragma unroll
+    for (int kk = 0; kk < NKK; ++kk) {
+      kf[kk] = *(const bf16x8*)(ks + kk * 32);
+      if constexpr (WHICH != 0) vf[kk] = *(const bf16x8*)(vs + kk * 32);
+    }
+  }
+  if (nt > 1) issue_tile(1, 1);
+
+  // ---- LDS read addresses (slot 0, first 32-row block) --------------------------------------------
+  uint32_t raddr[NKK];
+#pragma unroll
+  for (int kk = 0; kk < NKK; ++kk) raddr[kk] = ki * ROWB + (((2 * kk + h) ^ swz_rt(ki)) << 4);
+  uint32_t taddr[NCB][2];
+  {
+    const int s = lane & 15, chalf = (lane >> 4) & 1;
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+      for (int e = 0; e < 2; ++e) {
+        const int row = 8 * e + 4 * h + (s >> 2);
+        const int chunk = cb * 4 + chalf * 2 + ((s & 3) >> 1);
+        taddr[cb][e] = row * ROWB + ((chunk ^ swz_rt(row)) << 4) + ((s & 1) << 3);
+      }
+  }
+  auto row_operand = [&](int base, int kk) __attribute__((always_inline)) { return *(LDS_AS bf16x8*)(smem + raddr[kk] + base); };
+  auto tr_operand = [&](int base, int cb, int kc) __attribute__((always_inline)) {
+    const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(smem + taddr[cb][0] + base + kc * 16 * ROWB));
+    const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(smem + taddr[cb][1] + base + kc * 16 * ROWB));
+    s16x8 av;
+    av[0] = v0[0]; av[1] = v0[1]; av[2] = v0[2]; av[3] = v0[3];
+    av[4] = v1[0]; av[5] = v1[1]; av[6] = v1[2]; av[7] = v1[3];
+    return __builtin_bit_cast(bf16x8, av);
+  };
+
+  f32x16 acc[NCB];  // dV^T or dK^T
+#pragma unroll
+  for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[cb][r] = 0.f;
+  const float c = p.scale_log2;
+
+  // one 32-query block of the tile in `slot`: q0b = first query row, base = byte offset inside the Q slots
+  auto block = [&](int q0b, int slot, int kb) __attribute__((always_inline)) {
+    const int base = slot * TILEB + kb * SUBB;
+    f32x16 s, dp;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s[r] = dp[r] = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < NKK; ++kk) {
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_operand(base, kk), kf[kk], s, 0, 0, 0);
+      if constexpr (WHICH != 0) dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_operand(base + C::T2BASE, kk), vf[kk], dp, 0, 0, 0);
+    }
+    // accumulator row r of this lane is query q0b + 8 (r/4) + 4 h + r%4: its statistic and delta
+    const LDS_AS float* const aux = (const LDS_AS float*)(smem + C::AUXBASE + slot * 512) + kb * 32 + 4 * h;
+    const bool need_mask = CAUSAL && q0b < wk0 + 31;  // some query of the block comes before some key of the wave
+    u32x4 pk[2];
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+      const f32x4 l4 = *(const LDS_AS f32x4*)(aux + 8 * a);
+      f32x4 d4 = {0.f, 0.f, 0.f, 0.f};
+      if constexpr (WHICH != 0) d4 = *(const LDS_AS f32x4*)(aux + 64 + 8 * a);
+      float e[4];
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        const int r = 4 * a + t;
+        float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c, -l4[t]));
+        if (need_mask && q0b + 8 * a + 4 * h + t < krow) pr = 0.f;
+        e[t] = WHICH ? pr * (dp[r] - d4[t]) : pr;
+      }
+      pk[a >> 1][2 * (a & 1)] = pack_bf16(e[0], e[1]);
+      pk[a >> 1][2 * (a & 1) + 1] = pack_bf16(e[2], e[3]);
+    }
+    // dV^T += dO^T P (transposed dO tile)   /   dK^T += Q^T dS (transposed Q tile)
+    const int tbase = WHICH ? base : base + C::T2BASE;
+#pragma unroll
+    for (int i = 0; i < 2 * NCB; ++i) {
+      const int cb = i % NCB, kc = i / NCB;
+      acc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_operand(tbase, cb, kc), __builtin_bit_cast(bf16x8, pk[kc]), acc[cb], 0, 0, 0);
+    }
+  };
+
+  if (nt > 1) ATTN_WAIT_VMCNT(2 * NLD + 1);
+  else ATTN_WAIT_VMCNT(0);
+#pragma unroll
+  for (int kk = 0; kk < NKK; ++kk) asm volatile("" ::"v"(kf[kk]));
+  if constexpr (WHICH != 0) {
+#pragma unroll
+    for (int kk = 0; kk < NKK; ++kk) asm volatile("" ::"v"(vf[kk]));
+  }
+  attn_wg_barrier();
+
+  int slot = 0;
+  for (int j = 0; j < nt; ++j) {
+    const int pslot = slot == 0 ? NSLOT - 1 : slot - 1;
+    if (j + 2 < nt) issue_tile(j + 2, pslot);
+    const int qt = qt0 + j % nqt;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      const int q0b = qt * BN + kb * 32;
+      // skip blocks past the end of Q and, for causal inputs, blocks whose queries all come before the wave's keys
+      if (wave_valid && q0b < N && (!CAUSAL || q0b + 31 >= wk0)) block(q0b, slot, kb);
+    }
+    if (j + 2 < nt) ATTN_WAIT_VMCNT(2 * NLD + 1);
+    else ATTN_WAIT_VMCNT(0);
+    attn_wg_barrier();
+    slot = slot == NSLOT - 1 ? 0 : slot + 1;
+  }
+
+  char* const out = (char*)(WHICH ? p.dk : p.dv) + koff + (size_t)min(krow, N - 1) * ROWB;
+  store_transposed<NCB>(acc, WHICH ? p.scale : 1.0f, out, h, krow < N);
+}
+
+}  // namespace
+
+int attn_bwd_launch_bf16_d128(const AttnBwdParams& p, hipStream_t stream) {
+  const int grid_q = p.B * p.Hq * p.T, grid_k = p.B * p.Hkv * p.T;
+  if (p.causal) {
+    hipLaunchKernelGGL((attn_bwd_dq_kernel<true>), dim3(grid_q), dim3(512), 0, stream, p);
+    hipLaunchKernelGGL((attn_bwd_dkv_kernel<true, 0>), dim3(grid_k), dim3(512), 0, stream, p);
+    hipLaunchKernelGGL((attn_bwd_dkv_kernel<true, 1>), dim3(grid_k), dim3(512), 0, stream, p);
+  } else {
+    hipLaunchKernelGGL((attn_bwd_dq_kernel<false>), dim3(grid_q), dim3(512), 0, stream, p);
+    hipLaunchKernelGGL((attn_bwd_dkv_kernel<false, 0>), dim3(grid_k), dim3(512), 0, stream, p);
+    hipLaunchKernelGGL((attn_bwd_dkv_kernel<false, 1>), dim3(grid_k), dim3(512), 0, stream, p);
+  }
+  return (int)hipGetLastError();
+}

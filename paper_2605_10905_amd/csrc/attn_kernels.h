@@ -15,6 +15,27 @@ struct AttnParams {
   float out_scale;   // multiplies O in the epilogue (v_descale and P scaling for fp8; 1 for bf16)
 };
 
+// backward pass (bf16, head dimension 128)
+struct AttnBwdParams {
+  const void* q;
+  const void* k;
+  const void* v;
+  const void* o;
+  const void* dout;
+  const float* lse;
+  void* dq;
+  void* dk;
+  void* dv;
+  float* ws;         // [B, Hq, 2, Npad] floats: lse * log2(e) and delta, rows padded to whole 64-row tiles
+  int B, Hq, Hkv, N;
+  int T;             // 256-row tiles per head = ceil(N / 256)
+  int Npad;          // ceil(N / 64) * 64
+  int causal;
+  float scale_log2;  // scale * log2(e)
+  float scale;
+};
+int attn_bwd_launch_bf16_d128(const AttnBwdParams& p, hipStream_t stream);
+
 struct AttnVariant {
   const char* name;
   int dtype;   // attn_dtype

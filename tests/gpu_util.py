@@ -126,3 +126,76 @@ def check_whole_head(inp, o, lse, b, h, label=""):
     assert m["rel_fro"] <= tol["rel_fro"], f"{label}: {m}"
     assert m["lse_max_abs"] <= tol["lse"], f"{label}: {m}"
     return m
+
+
+# ---- backward --------------------------------------------------------------------------------
+# bf16 gradients: relative Frobenius error 5e-3 per tensor, and every element within
+# 2e-2 * max(1, max|reference|) (the gradients' scale varies with the mask and the length, so
+# the element-wise bound scales with the tensor's largest entry).  Below 64 keys every row is a
+# few-key row: there dP - delta cancels by the factor 1 - max(P), which amplifies the 2^-9
+# rounding of the stored bf16 O (delta = rowsum(dO * O)) by its inverse, so the Frobenius bound
+# is 1e-2 for those lengths; the element-wise bound is the same everywhere.
+TOL_BWD = dict(rel_fro=5e-3, rel_fro_short=1e-2, short_n=64, max_abs_rel=2e-2)
+
+
+def bf16_to_device(bits):
+    return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).cuda()
+
+
+def run_gpu_bwd(inp, dout_bits, dev=None, poison=float("nan")):
+    """Forward then backward through the C ABI.  Returns (dq, dk, dv, o, lse) on the device."""
+    import paper_2605_10905_amd as A
+
+    dev = dev or to_device(inp)
+    B, Hq, Hkv, N, d = inp["B"], inp["Hq"], inp["Hkv"], inp["N"], inp["d"]
+    o, lse = run_gpu(inp, dev)
+    do = bf16_to_device(dout_bits)
+    dq = torch.full((B, Hq, N, d), poison, dtype=torch.bfloat16, device="cuda")
+    dk = torch.full((B, Hkv, N, d), poison, dtype=torch.bfloat16, device="cuda")
+    dv = torch.full((B, Hkv, N, d), poison, dtype=torch.bfloat16, device="cuda")
+    ws = torch.full((A.attn_bwd_workspace_bytes(B, Hq, N) // 4,), poison, dtype=torch.float32, device="cuda")
+    A.attn_bwd(dev["q"], dev["k"], dev["v"], o, do, lse, dq, dk, dv, ws, B, Hq, Hkv, N, d, inp["causal"], inp["scale"],
+               A.ATTN_BF16)
+    torch.cuda.synchronize()
+    return dq, dk, dv, o, lse
+
+
+def check_grads(got, ref, label="", peaked=False):
+    """got, ref: dicts name -> array; every tensor against TOL_BWD (`peaked`: the few-key
+    Frobenius bound, for inputs built so that single keys dominate their rows)."""
+    from oracle import attn_bwd_ref as ob
+
+    out = {}
+    for nm in ref:
+        g = got[nm].float().cpu().numpy().astype(np.float64) if torch.is_tensor(got[nm]) else got[nm]
+        assert np.isfinite(g).all(), f"{label}: non-finite {nm}"
+        m = ob.grad_error_metrics(g, ref[nm])
+        bound = TOL_BWD["max_abs_rel"] * max(1.0, float(np.abs(ref[nm]).max()))
+        assert m["max_abs"] <= bound, f"{label}: {nm} {m} bound {bound}"
+        n_keys = ref[nm].shape[-2]
+        fro = TOL_BWD["rel_fro_short"] if (peaked or n_keys < TOL_BWD["short_n"]) else TOL_BWD["rel_fro"]
+        assert m["rel_fro"] <= fro, f"{label}: {nm} {m}"
+        out[nm] = m
+    return out
+
+
+def check_bwd_full(inp, dout_bits, dq, dk, dv, label="", peaked=False):
+    from oracle import attn_bwd_ref as ob
+
+    x = decode(inp)
+    rq, rk, rv = ob.attn_bwd_ref(x["q"], x["k"], x["v"], orc.bf16_bits_to_f64(dout_bits), inp["causal"], inp["scale"])
+    return check_grads(dict(dq=dq, dk=dk, dv=dv), dict(dq=rq, dk=rk, dv=rv), label, peaked)
+
+
+def check_bwd_group(inp, dout_bits, dq, dk, dv, b, g, label=""):
+    """Full-size check of one whole (batch, kv head) group: dK, dV of that kv head and dQ of
+    every query head that reads it."""
+    from oracle import attn_bwd_ref as ob
+
+    G = inp["Hq"] // inp["Hkv"]
+    hs = slice(g * G, (g + 1) * G)
+    x = decode(inp)
+    rq, rk, rv = ob.attn_bwd_ref(x["q"][b:b + 1, hs], x["k"][b:b + 1, g:g + 1], x["v"][b:b + 1, g:g + 1],
+                                 orc.bf16_bits_to_f64(dout_bits[b:b + 1, hs]), inp["causal"], inp["scale"])
+    return check_grads(dict(dq=dq[b:b + 1, hs], dk=dk[b:b + 1, g:g + 1], dv=dv[b:b + 1, g:g + 1]),
+                       dict(dq=rq, dk=rk, dv=rv), label)

@@ -107,3 +107,17 @@ def make_inputs(cfg, B=None, Hq=None, Hkv=None, N=None):
     else:
         raise ValueError(cfg["dtype"])
     return out
+
+
+def make_dout(cfg, B=None, Hq=None, N=None, sigma=1.0):
+    """Output gradient for the backward pass: bf16 bit patterns [B,Hq,N,d], i.i.d. normal,
+    drawn from a stream of its own of the config's seed."""
+    B = cfg["B"] if B is None else B
+    Hq = cfg["Hq"] if Hq is None else Hq
+    N = cfg["N"] if N is None else N
+    return make_bf16(cfg["seed"], 3, (B, Hq, N, cfg["d"]), sigma)
+
+
+def algorithmic_flops_bwd(cfg) -> float:
+    """Backward: five N x N x d products (S, dP, dV, dQ, dK) = 10*B*Hq*N^2*d, halved for causal."""
+    return 2.5 * algorithmic_flops(cfg)
