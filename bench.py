@@ -119,6 +119,54 @@ def time_paper_grid(A, torch):
     return rows
 
 
+def time_backward(A, torch, cfgs):
+    """Backward pass (bf16, d = 128) on the given shapes: one step = attn_bwd (three kernels).
+    Inputs are drawn on the device (seeded N(0,1), rounded to bf16) and O, lse come from
+    attn_fwd on them; parity on these shapes is covered by the tests.  TFLOP/s counts the five
+    N x N x d products of the textbook backward (2.5 x the forward figure)."""
+    import workloads as wl
+
+    rows = []
+    gen = torch.Generator(device="cuda")
+    for cfg in cfgs:
+        B, Hq, Hkv, N, d = cfg["B"], cfg["Hq"], cfg["Hkv"], cfg["N"], cfg["d"]
+        gen.manual_seed(cfg["seed"])
+        sig = cfg.get("sigma", 1.0)
+        q = (torch.randn((B, Hq, N, d), device="cuda", generator=gen) * sig).to(torch.bfloat16)
+        k, v = ((torch.randn((B, Hkv, N, d), device="cuda", generator=gen) * sig).to(torch.bfloat16) for _ in range(2))
+        do = torch.randn((B, Hq, N, d), device="cuda", generator=gen).to(torch.bfloat16)
+        o, dq = torch.empty_like(q), torch.empty_like(q)
+        dk, dv = torch.empty_like(k), torch.empty_like(v)
+        lse = torch.empty((B, Hq, N), dtype=torch.float32, device="cuda")
+        ws = torch.empty(A.attn_bwd_workspace_bytes(B, Hq, N) // 4, dtype=torch.float32, device="cuda")
+        stream = torch.cuda.current_stream()
+        A.attn_fwd(q, k, v, o, lse, B, Hq, Hkv, N, d, cfg["causal"], cfg["scale"], A.ATTN_BF16, stream=stream)
+
+        def step():
+            A.attn_bwd(q, k, v, o, do, lse, dq, dk, dv, ws, B, Hq, Hkv, N, d, cfg["causal"], cfg["scale"], A.ATTN_BF16,
+                       stream=stream)
+
+        flops = wl.algorithmic_flops_bwd(cfg)
+        est = flops / 0.5e15
+        for _ in range(max(3, min(100, int(0.05 / est)))):
+            step()
+        torch.cuda.synchronize()
+        n = max(5, min(30, int(0.05 / est)))
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+        for a, b in evs:
+            a.record(stream)
+            step()
+            b.record(stream)
+        torch.cuda.synchronize()
+        ms = float(np.median([a.elapsed_time(b) for a, b in evs]))
+        tf = flops / (ms * 1e-3) / 1e12
+        rows.append({"workload": cfg["name"], "ms": ms, "TFLOP/s": tf, "pct_of_dense_peak": 100 * tf / PEAK_TFLOPS["bf16"],
+                     "algorithmic_flop": flops})
+        log(f"[bench] backward {cfg['name']}: {ms:.4f} ms  {tf:.1f} TFLOP/s = {100 * tf / PEAK_TFLOPS['bf16']:.1f}%")
+        del q, k, v, do, o, dq, dk, dv, lse, ws
+    return rows
+
+
 def cpu_baseline(cfg, inp, budget_s=20.0):
     """The oracle as it stands, timed on the host cores on a bounded sample: whole
     (b, h) heads of the same workload, one after another, until the time budget is
@@ -168,6 +216,10 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--all-configs", action="store_true", help="also time the other bf16 configs (reported in 'others')")
     ap.add_argument("--paper-grid", action="store_true", help="also time the paper's attention shape grid (reported in 'paper_grid')")
+    ap.add_argument("--backward", action="store_true",
+                    help="also time attn_bwd on the chosen config (with --all-configs: every bf16 d=128 config; with "
+                         "--paper-grid: the paper's grid as well); "
+                         "reported in 'backward'")
     ap.add_argument("--copy-calibration", action="store_true", help="only run a 1 GiB copy (counter calibration)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -236,6 +288,11 @@ def main():
         out["others"] = others
     if args.paper_grid:
         out["paper_grid"] = time_paper_grid(A, torch)
+    if args.backward:
+        cfgs = [c for c in wl.CONFIGS if c["dtype"] == "bf16" and c["d"] == 128 and (args.all_configs or c is cfg)]
+        if args.paper_grid:
+            cfgs += wl.paper_grid()
+        out["backward"] = time_backward(A, torch, cfgs)
     if not args.no_cpu_baseline:
         log("[bench] timing the CPU oracle on a bounded sample ...")
         out["cpu_baseline"] = cpu_baseline(cfg, r["inp"])
