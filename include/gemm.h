@@ -1,0 +1,55 @@
+/*
+ * C ABI of the bf16 GEMM of libattn_mi355x.so (MI355X, gfx950).
+ *
+ * The operation (paper section 6.1, GEMM paragraph: a producer/consumer pipelined GEMM;
+ * section 6.3 and appendix A, GEMM shape tables: 8192 x 8192 x K and, on MI350,
+ * 256^3 ... 2048^3):
+ *
+ *     C[m, n] = sum_k A[m, k] * B[n, k]        fp32 accumulation, C rounded to bfloat16
+ *
+ * All pointers are DEVICE pointers to dense row-major arrays the caller owns and keeps alive
+ * until the stream has run the call.  Nothing is allocated, nothing is copied to the host, and
+ * the call returns without synchronising.  Status codes are attn_status (attn.h).
+ */
+#ifndef PAPER_2605_10905_GEMM_H
+#define PAPER_2605_10905_GEMM_H
+
+#include "attn.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/*
+ * gemm_bf16_nt -- C = A B^T.
+ *   a        device, bfloat16 [M, K] row-major (K contiguous), 16-byte aligned
+ *   b        device, bfloat16 [N, K] row-major (K contiguous: the layout of a linear layer's
+ *            weight), 16-byte aligned
+ *   c        device, bfloat16 [M, N] row-major, overwritten; 16-byte aligned
+ *   M, N     any positive size (ragged tiles are handled in the kernel)
+ *   K        positive multiple of 32 (ATTN_ERR_UNSUPPORTED otherwise: operand tiles are moved
+ *            in whole 32-column slices)
+ *   stream   hipStream_t (NULL = default stream)
+ * Errors: ATTN_ERR_NULL, ATTN_ERR_SHAPE (non-positive size, misaligned pointer),
+ * ATTN_ERR_UNSUPPORTED (K, or a size beyond 2^31 bytes per operand tile row span),
+ * ATTN_ERR_LAUNCH.  Argument checks run before anything is enqueued.
+ */
+int gemm_bf16_nt(const void* a, const void* b, void* c, int M, int N, int K, void* stream);
+
+/* Tuning hook: the same with kernel variant `variant` (0 .. gemm_num_variants()-1). */
+int gemm_bf16_nt_variant(const void* a, const void* b, void* c, int M, int N, int K, int variant, void* stream);
+int gemm_num_variants(void);
+const char* gemm_variant_name(int variant); /* NULL if out of range */
+
+/*
+ * Work decomposition (host-side, for tests): tile (tm, tn) of BM x BN = 256 x 256 that
+ * workgroup `wg` of a launch over an M x N output computes.  Returns ATTN_ERR_SHAPE if wg is
+ * out of range.
+ */
+int gemm_tile_coord(int wg, int M, int N, int* tm, int* tn);
+int gemm_num_workgroups(int M, int N);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

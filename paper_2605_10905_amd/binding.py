@@ -38,6 +38,18 @@ lib.attn_bwd.argtypes = [_vp] * 10 + [_i, _i, _i, _i, _i, _i, _f, _i, _vp]
 lib.attn_bwd.restype = _i
 lib.attn_bwd_workspace_bytes.argtypes = [_i, _i, _i]
 lib.attn_bwd_workspace_bytes.restype = C.c_longlong
+lib.gemm_bf16_nt.argtypes = [_vp, _vp, _vp, _i, _i, _i, _vp]
+lib.gemm_bf16_nt.restype = _i
+lib.gemm_bf16_nt_variant.argtypes = [_vp, _vp, _vp, _i, _i, _i, _i, _vp]
+lib.gemm_bf16_nt_variant.restype = _i
+lib.gemm_num_variants.argtypes = []
+lib.gemm_num_variants.restype = _i
+lib.gemm_variant_name.argtypes = [_i]
+lib.gemm_variant_name.restype = C.c_char_p
+lib.gemm_num_workgroups.argtypes = [_i, _i]
+lib.gemm_num_workgroups.restype = _i
+lib.gemm_tile_coord.argtypes = [_i, _i, _i, C.POINTER(_i), C.POINTER(_i)]
+lib.gemm_tile_coord.restype = _i
 lib.attn_num_variants.argtypes = []
 lib.attn_num_variants.restype = _i
 lib.attn_variant_name.argtypes = [_i]
@@ -142,3 +154,38 @@ def attn_bwd(q, k, v, o, dout, lse, dq, dk, dv, workspace, B, Hq, Hkv, N, d, cau
     if check and st != 0:
         raise AttnError(st, "attn_bwd")
     return st
+
+
+def gemm_bf16_nt(a, b, c, M, N, K, stream=None, check=True):
+    st = lib.gemm_bf16_nt(_ptr(a), _ptr(b), _ptr(c), M, N, K, _stream(stream))
+    if check and st != 0:
+        raise AttnError(st, "gemm_bf16_nt")
+    return st
+
+
+def gemm_bf16_nt_variant(a, b, c, M, N, K, variant, stream=None, check=True):
+    st = lib.gemm_bf16_nt_variant(_ptr(a), _ptr(b), _ptr(c), M, N, K, int(variant), _stream(stream))
+    if check and st != 0:
+        raise AttnError(st, "gemm_bf16_nt_variant")
+    return st
+
+
+def gemm_num_variants() -> int:
+    return lib.gemm_num_variants()
+
+
+def gemm_variant_name(variant: int):
+    s = lib.gemm_variant_name(int(variant))
+    return None if s is None else s.decode()
+
+
+def gemm_num_workgroups(M: int, N: int) -> int:
+    return lib.gemm_num_workgroups(M, N)
+
+
+def gemm_tile_coord(wg, M, N):
+    tm, tn = _i(), _i()
+    st = lib.gemm_tile_coord(wg, M, N, C.byref(tm), C.byref(tn))
+    if st != 0:
+        raise AttnError(st, "gemm_tile_coord")
+    return tm.value, tn.value

@@ -1,0 +1,19 @@
+// Internal interface between the GEMM C-ABI entry points and the gfx950 kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+
+struct GemmParams {
+  const void* a;  // bf16 [M, K]
+  const void* b;  // bf16 [N, K]
+  void* c;        // bf16 [M, N]
+  int M, N, K;
+  int tiles_m, tiles_n;
+};
+
+struct GemmVariant {
+  const char* name;
+  int bm, bn, bk;
+  int (*launch)(const GemmParams& p, hipStream_t stream);
+};
+
+const GemmVariant* gemm_bf16_nt_variants(int* count);

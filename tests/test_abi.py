@@ -18,9 +18,12 @@ def A():
 
 
 def header_functions():
-    text = open(os.path.join(ROOT, "include", "attn.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(attn_[a-z0-9_]+)\s*\(", text)))
+    names = set()
+    for h in sorted(os.listdir(os.path.join(ROOT, "include"))):
+        text = open(os.path.join(ROOT, "include", h)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names.update(re.findall(r"\b((?:attn|gemm)_[a-z0-9_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_every_declared_symbol_is_exported(A):
@@ -36,7 +39,7 @@ def test_header_compiles_as_c():
 
     with tempfile.TemporaryDirectory() as td:
         src = os.path.join(td, "t.c")
-        open(src, "w").write('#include "attn.h"\nint main(void){return attn_version() == 0;}\n')
+        open(src, "w").write('#include "attn.h"\n#include "gemm.h"\nint main(void){return attn_version() == 0;}\n')
         subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"), "-c", src,
                         "-o", os.path.join(td, "t.o")], check=True)
 

@@ -1,0 +1,114 @@
+"""GPU parity of the bf16 GEMM: the HIP path, called through the C ABI, against the float64
+CPU oracle on the same seeded inputs.
+
+Tolerance (derived from the arithmetic): products of bf16 values are exact in fp32, the fp32
+accumulation of K terms errs by at most K * 2^-24 * sum_k |a||b| whatever the order, and the
+result is rounded once to bf16 (relative 2^-9).  Element-wise bound:
+    |c - ref| <= 2^-8 |ref| + K * 2^-23 * sum_k |a_k||b_k|
+(twice each term), and relative Frobenius error <= 3e-3 (bf16 rounding alone gives 1.1e-3 RMS)."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from oracle import gemm_ref as og
+from tests import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+
+def _variants():
+    import paper_2605_10905_amd as A
+
+    return [None] + list(range(A.gemm_num_variants()))
+
+
+def run_gemm(a_bits, b_bits, variant=None, poison=float("nan")):
+    import paper_2605_10905_amd as A
+
+    M, K = a_bits.shape
+    N = b_bits.shape[0]
+    a, b = gu.bf16_to_device(a_bits), gu.bf16_to_device(b_bits)
+    c = torch.full((M, N), poison, dtype=torch.bfloat16, device="cuda")
+    if variant is None:
+        A.gemm_bf16_nt(a, b, c, M, N, K)
+    else:
+        A.gemm_bf16_nt_variant(a, b, c, M, N, K, variant)
+    torch.cuda.synchronize()
+    return c
+
+
+def check(c, a_bits, b_bits, label, rows=None):
+    a, b = og.bf16_bits_to_f64(a_bits), og.bf16_bits_to_f64(b_bits)
+    K = a.shape[1]
+    if rows is None:
+        ref, mag = og.gemm_ref(a, b), og.gemm_abs_ref(a, b)
+        got = c.float().cpu().numpy().astype(np.float64)
+    else:
+        ref, mag = og.gemm_rows(a, b, rows), og.gemm_rows(np.abs(a), np.abs(b), rows)
+        got = c[torch.from_numpy(np.asarray(rows)).cuda()].float().cpu().numpy().astype(np.float64)
+    assert np.isfinite(got).all(), f"{label}: non-finite C"
+    bound = 2.0 ** -8 * np.abs(ref) + K * 2.0 ** -23 * mag + 1e-30
+    worst = float(np.max(np.abs(got - ref) / bound))
+    assert worst <= 1.0, f"{label}: element-wise error {worst:.3f} x bound"
+    m = og.error_metrics(got, ref)
+    assert m["rel_fro"] <= 3e-3, f"{label}: {m}"
+    return m
+
+
+# several tiles, ragged M and N, one to many k-steps
+SMALL = [(256, 256, 256), (512, 512, 512), (300, 520, 96), (1, 8, 32), (257, 264, 1024), (1000, 72, 64), (33, 1000, 2048),
+         (777, 513, 160), (64, 7, 32), (5, 3, 64), (1024, 1024, 32)]
+
+
+@pytest.mark.parametrize("M,N,K", SMALL)
+def test_gemm_small_shapes_all_variants(M, N, K):
+    a, b = wl.make_gemm_inputs(500 + M + N + K, M, N, K)
+    for var in _variants():
+        print(f"gemm {M}x{N}x{K} variant {var}", flush=True)
+        c = run_gemm(a, b, var)
+        check(c, a, b, f"gemm {M}x{N}x{K} variant {var}")
+
+
+def test_gemm_structured_inputs():
+    """Operands that expose a wrong row/column or k mapping: one-hot rows select single entries."""
+    M, N, K = 384, 320, 128
+    rng = np.random.default_rng(3)
+    a = rng.standard_normal((M, K)).astype(np.float32)
+    b = np.zeros((N, K), dtype=np.float32)
+    cols = rng.integers(0, K, N)
+    b[np.arange(N), cols] = 1.0
+    ab, bb = wl.f32_to_bf16_bits(a), wl.f32_to_bf16_bits(b)
+    for var in _variants():
+        c = run_gemm(ab, bb, var)
+        want = torch.from_numpy(ab.view(np.int16)).view(torch.bfloat16)[:, torch.from_numpy(cols)]
+        assert torch.equal(c.cpu().view(torch.int16), want.contiguous().view(torch.int16)), f"variant {var}"
+
+
+def test_gemm_determinism_and_unsupported():
+    import paper_2605_10905_amd as A
+
+    a, b = wl.make_gemm_inputs(9, 512, 384, 256)
+    c1, c2 = run_gemm(a, b), run_gemm(a, b, poison=1.0e30)
+    assert torch.equal(c1.view(torch.int16), c2.view(torch.int16))
+    t = torch.zeros(64 * 64, dtype=torch.bfloat16, device="cuda")
+    assert A.gemm_bf16_nt(t, t, t, 64, 64, 24, check=False) != 0       # K not a multiple of 32
+    assert A.gemm_bf16_nt(t, t, None, 64, 64, 32, check=False) != 0
+    assert A.gemm_bf16_nt(t, t, t, 0, 64, 32, check=False) != 0
+
+
+@pytest.mark.parametrize("name", ["mi350_2048", "canonical_k8192", "large_k_512x4096x64512", "large_n_2048x64512x256"])
+def test_gemm_full_size_sampled(name):
+    """Paper shapes at full size, in the launch configuration bench.py times: the oracle on sampled
+    rows of C (tile edges and random rows), every column."""
+    g = next(s for s in wl.GEMM_SHAPES if s["name"] == name)
+    M, N, K = g["M"], g["N"], g["K"]
+    print(f"gemm full size {name}: generating inputs", flush=True)
+    a, b = wl.make_gemm_inputs(g["seed"], M, N, K)
+    print(f"gemm full size {name}: launching", flush=True)
+    c = run_gemm(a, b)
+    assert bool(torch.isfinite(c.float()).all())
+    rng = np.random.default_rng(g["seed"])
+    rows = sorted({0, 1, 255, 256, 127, 128, M - 1, M // 2, *(int(r) for r in rng.integers(0, M, 24))} & set(range(M)))
+    print(f"gemm full size {name}: oracle on {len(rows)} rows", flush=True)
+    print(check(c, a, b, f"gemm {name}", rows=rows), flush=True)

@@ -121,3 +121,30 @@ def make_dout(cfg, B=None, Hq=None, N=None, sigma=1.0):
 def algorithmic_flops_bwd(cfg) -> float:
     """Backward: five N x N x d products (S, dP, dV, dQ, dK) = 10*B*Hq*N^2*d, halved for causal."""
     return 2.5 * algorithmic_flops(cfg)
+
+
+# ---- GEMM (paper appendix A: GEMM shape tables) -----------------------------------------------
+# (name, M, N, K): the MI350 progression, the canonical 8192 x 8192 x K family, and the skewed
+# production shapes of the B200 table whose operands fit comfortably on one GPU
+GEMM_SHAPES = (
+    [dict(name=f"mi350_{n}", M=n, N=n, K=n) for n in (256, 512, 1024, 2048)]
+    + [dict(name=f"canonical_k{k}", M=8192, N=8192, K=k) for k in (1024, 2048, 4096, 8192, 16384)]
+    + [dict(name="large_m_442368x448x192", M=442368, N=448, K=192),
+       dict(name="large_m_589824x256x128", M=589824, N=256, K=128),
+       dict(name="large_m_589824x512x2048", M=589824, N=512, K=2048),
+       dict(name="large_n_1152x32768x9216", M=1152, N=32768, K=9216),
+       dict(name="large_n_2048x64512x256", M=2048, N=64512, K=256),
+       dict(name="large_k_512x4096x64512", M=512, N=4096, K=64512),
+       dict(name="large_k_2304x1024x65536", M=2304, N=1024, K=65536)]
+)
+for _i, _g in enumerate(GEMM_SHAPES):
+    _g["seed"] = 3000 + _i
+
+
+def make_gemm_inputs(seed: int, M: int, N: int, K: int, sigma: float = 1.0):
+    """A [M,K] and B [N,K] as bf16 bit patterns, i.i.d. normal."""
+    return make_bf16(seed, 0, (M, K), sigma), make_bf16(seed, 1, (N, K), sigma)
+
+
+def gemm_flops(M: int, N: int, K: int) -> float:
+    return 2.0 * M * N * K
