@@ -167,6 +167,49 @@ def time_backward(A, torch, cfgs):
     return rows
 
 
+def time_gemm(A, torch, shapes, variants=(None,)):
+    """bf16 GEMM on the paper's shapes.  Inputs drawn on the device (seeded N(0,1) rounded to
+    bf16); parity on these shapes is covered by the tests."""
+    import workloads as wl
+
+    rows = []
+    gen = torch.Generator(device="cuda")
+    for g in shapes:
+        M, N, K = g["M"], g["N"], g["K"]
+        gen.manual_seed(g["seed"])
+        a = torch.randn((M, K), device="cuda", generator=gen).to(torch.bfloat16)
+        b = torch.randn((N, K), device="cuda", generator=gen).to(torch.bfloat16)
+        c = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+        stream = torch.cuda.current_stream()
+        flops = wl.gemm_flops(M, N, K)
+        for var in variants:
+            def step():
+                if var is None:
+                    A.gemm_bf16_nt(a, b, c, M, N, K, stream=stream)
+                else:
+                    A.gemm_bf16_nt_variant(a, b, c, M, N, K, var, stream=stream)
+
+            est = flops / 1.0e15 + 5e-6
+            for _ in range(max(3, min(200, int(0.05 / est)))):
+                step()
+            torch.cuda.synchronize()
+            n = max(5, min(50, int(0.05 / est)))
+            evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+            for e0, e1 in evs:
+                e0.record(stream)
+                step()
+                e1.record(stream)
+            torch.cuda.synchronize()
+            ms = float(np.median([e0.elapsed_time(e1) for e0, e1 in evs]))
+            tf = flops / (ms * 1e-3) / 1e12
+            rows.append({"workload": g["name"], "variant": "library default" if var is None else A.gemm_variant_name(var),
+                         "ms": ms, "TFLOP/s": tf, "pct_of_dense_peak": 100 * tf / PEAK_TFLOPS["bf16"]})
+            log(f"[bench] gemm {g['name']} [{rows[-1]['variant']}]: {ms:.4f} ms  {tf:.1f} TFLOP/s = "
+                f"{100 * tf / PEAK_TFLOPS['bf16']:.1f}%")
+        del a, b, c
+    return rows
+
+
 def cpu_baseline(cfg, inp, budget_s=20.0):
     """The oracle as it stands, timed on the host cores on a bounded sample: whole
     (b, h) heads of the same workload, one after another, until the time budget is
@@ -220,6 +263,9 @@ def main():
                     help="also time attn_bwd on the chosen config (with --all-configs: every bf16 d=128 config; with "
                          "--paper-grid: the paper's grid as well); "
                          "reported in 'backward'")
+    ap.add_argument("--gemm", action="store_true", help="also time the bf16 GEMM on the paper's shapes (reported in 'gemm')")
+    ap.add_argument("--gemm-shape", default=None, help="with --gemm: only this shape (a name in workloads.GEMM_SHAPES)")
+    ap.add_argument("--gemm-variants", action="store_true", help="with --gemm: time every kernel variant")
     ap.add_argument("--copy-calibration", action="store_true", help="only run a 1 GiB copy (counter calibration)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -293,6 +339,10 @@ def main():
         if args.paper_grid:
             cfgs += wl.paper_grid()
         out["backward"] = time_backward(A, torch, cfgs)
+    if args.gemm:
+        variants = [None] + list(range(A.gemm_num_variants())) if args.gemm_variants else [None]
+        shapes = [g for g in wl.GEMM_SHAPES if args.gemm_shape in (None, g["name"])]
+        out["gemm"] = time_gemm(A, torch, shapes, variants)
     if not args.no_cpu_baseline:
         log("[bench] timing the CPU oracle on a bounded sample ...")
         out["cpu_baseline"] = cpu_baseline(cfg, r["inp"])

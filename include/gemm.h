@@ -28,7 +28,7 @@ extern "C" {
  *   c        device, bfloat16 [M, N] row-major, overwritten; 16-byte aligned
  *   M, N     any positive size (ragged tiles are handled in the kernel)
  *   K        positive multiple of 32 (ATTN_ERR_UNSUPPORTED otherwise: operand tiles are moved
- *            in whole 32-column slices)
+ *            in whole 32- or 64-column slices)
  *   stream   hipStream_t (NULL = default stream)
  * Errors: ATTN_ERR_NULL, ATTN_ERR_SHAPE (non-positive size, misaligned pointer),
  * ATTN_ERR_UNSUPPORTED (K, or a size beyond 2^31 bytes per operand tile row span),
@@ -36,18 +36,20 @@ extern "C" {
  */
 int gemm_bf16_nt(const void* a, const void* b, void* c, int M, int N, int K, void* stream);
 
-/* Tuning hook: the same with kernel variant `variant` (0 .. gemm_num_variants()-1). */
+/* Tuning hook: the same with kernel variant `variant` (0 .. gemm_num_variants()-1);
+ * ATTN_ERR_UNSUPPORTED if K is not a multiple of that variant's K-slice. */
 int gemm_bf16_nt_variant(const void* a, const void* b, void* c, int M, int N, int K, int variant, void* stream);
 int gemm_num_variants(void);
 const char* gemm_variant_name(int variant); /* NULL if out of range */
 
 /*
- * Work decomposition (host-side, for tests): tile (tm, tn) of BM x BN = 256 x 256 that
+ * Work decomposition (host-side, for tests): tile (tm, tn) of tile x tile outputs that
  * workgroup `wg` of a launch over an M x N output computes.  Returns ATTN_ERR_SHAPE if wg is
- * out of range.
+ * out of range.  gemm_variant_tile gives a variant's square tile size (0 if out of range).
  */
-int gemm_tile_coord(int wg, int M, int N, int* tm, int* tn);
-int gemm_num_workgroups(int M, int N);
+int gemm_tile_coord(int wg, int M, int N, int tile, int* tm, int* tn);
+int gemm_num_workgroups(int M, int N, int tile);
+int gemm_variant_tile(int variant);
 
 #ifdef __cplusplus
 }

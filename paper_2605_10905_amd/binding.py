@@ -46,9 +46,11 @@ lib.gemm_num_variants.argtypes = []
 lib.gemm_num_variants.restype = _i
 lib.gemm_variant_name.argtypes = [_i]
 lib.gemm_variant_name.restype = C.c_char_p
-lib.gemm_num_workgroups.argtypes = [_i, _i]
+lib.gemm_num_workgroups.argtypes = [_i, _i, _i]
 lib.gemm_num_workgroups.restype = _i
-lib.gemm_tile_coord.argtypes = [_i, _i, _i, C.POINTER(_i), C.POINTER(_i)]
+lib.gemm_variant_tile.argtypes = [_i]
+lib.gemm_variant_tile.restype = _i
+lib.gemm_tile_coord.argtypes = [_i, _i, _i, _i, C.POINTER(_i), C.POINTER(_i)]
 lib.gemm_tile_coord.restype = _i
 lib.attn_num_variants.argtypes = []
 lib.attn_num_variants.restype = _i
@@ -179,13 +181,17 @@ def gemm_variant_name(variant: int):
     return None if s is None else s.decode()
 
 
-def gemm_num_workgroups(M: int, N: int) -> int:
-    return lib.gemm_num_workgroups(M, N)
+def gemm_num_workgroups(M: int, N: int, tile: int) -> int:
+    return lib.gemm_num_workgroups(M, N, tile)
 
 
-def gemm_tile_coord(wg, M, N):
+def gemm_variant_tile(variant: int) -> int:
+    return lib.gemm_variant_tile(int(variant))
+
+
+def gemm_tile_coord(wg, M, N, tile):
     tm, tn = _i(), _i()
-    st = lib.gemm_tile_coord(wg, M, N, C.byref(tm), C.byref(tn))
+    st = lib.gemm_tile_coord(wg, M, N, tile, C.byref(tm), C.byref(tn))
     if st != 0:
         raise AttnError(st, "gemm_tile_coord")
     return tm.value, tn.value

@@ -10,12 +10,33 @@ namespace {
 
 bool misaligned(const void* p, uintptr_t a) { return ((uintptr_t)p & (a - 1)) != 0; }
 
+// Kernel choice, from measurements on the paper's shapes: the 256 x 256 tile (best rate per CU)
+// when it gives most of the 256 CUs a tile; the 128 x 128 tile with a deep ring when that yields
+// at least 100 tiles (it then beats both the half-empty chip of the large tile and the operand
+// re-reads of the small one); else 64 x 64.
+int find(const GemmVariant* table, int count, int tile, int bk, int nth) {
+  for (int i = 0; i < count; ++i)
+    if (table[i].bm == tile && table[i].bk == bk && nth-- == 0) return i;
+  return -1;
+}
+
+int choose(int M, int N, int K, const GemmVariant* table, int count) {
+  auto tiles = [&](int t) { return (long long)((M + t - 1) / t) * ((N + t - 1) / t); };
+  int v = -1;
+  if (tiles(256) >= 200) v = find(table, count, 256, 32, 0);
+  else if (tiles(128) >= 100 && K % 64 == 0) v = find(table, count, 128, 64, 1);
+  if (v < 0) v = find(table, count, 64, 32, 0);
+  return v;
+}
+
 int run(const void* a, const void* b, void* c, int M, int N, int K, int variant, void* stream) {
   if (!a || !b || !c) return ATTN_ERR_NULL;
   if (M <= 0 || N <= 0 || K <= 0) return ATTN_ERR_SHAPE;
   if (misaligned(a, 16) || misaligned(b, 16) || misaligned(c, 16)) return ATTN_ERR_SHAPE;
   int count = 0;
   const GemmVariant* table = gemm_bf16_nt_variants(&count);
+  if (K % 32 != 0) return ATTN_ERR_UNSUPPORTED;
+  if (variant == -1) variant = choose(M, N, K, table, count);
   if (variant < 0 || variant >= count) return ATTN_ERR_UNSUPPORTED;
   const GemmVariant& v = table[variant];
   if (K % v.bk != 0) return ATTN_ERR_UNSUPPORTED;
@@ -35,10 +56,11 @@ int run(const void* a, const void* b, void* c, int M, int N, int K, int variant,
 extern "C" {
 
 int gemm_bf16_nt(const void* a, const void* b, void* c, int M, int N, int K, void* stream) {
-  return run(a, b, c, M, N, K, 0, stream);
+  return run(a, b, c, M, N, K, -1, stream);
 }
 
 int gemm_bf16_nt_variant(const void* a, const void* b, void* c, int M, int N, int K, int variant, void* stream) {
+  if (variant < 0) return ATTN_ERR_UNSUPPORTED;
   return run(a, b, c, M, N, K, variant, stream);
 }
 
@@ -54,15 +76,21 @@ const char* gemm_variant_name(int variant) {
   return variant >= 0 && variant < count ? table[variant].name : nullptr;
 }
 
-int gemm_num_workgroups(int M, int N) {
-  if (M <= 0 || N <= 0) return 0;
-  return ((M + 255) / 256) * ((N + 255) / 256);
+int gemm_variant_tile(int variant) {
+  int count = 0;
+  const GemmVariant* table = gemm_bf16_nt_variants(&count);
+  return variant >= 0 && variant < count ? table[variant].bm : 0;
 }
 
-int gemm_tile_coord(int wg, int M, int N, int* tm, int* tn) {
+int gemm_num_workgroups(int M, int N, int tile) {
+  if (M <= 0 || N <= 0 || tile <= 0) return 0;
+  return ((M + tile - 1) / tile) * ((N + tile - 1) / tile);
+}
+
+int gemm_tile_coord(int wg, int M, int N, int tile, int* tm, int* tn) {
   if (!tm || !tn) return ATTN_ERR_NULL;
-  if (M <= 0 || N <= 0) return ATTN_ERR_SHAPE;
-  const int tiles_m = (M + 255) / 256, tiles_n = (N + 255) / 256;
+  if (M <= 0 || N <= 0 || tile <= 0) return ATTN_ERR_SHAPE;
+  const int tiles_m = (M + tile - 1) / tile, tiles_n = (N + tile - 1) / tile;
   if (wg < 0 || wg >= tiles_m * tiles_n) return ATTN_ERR_SHAPE;
   const GemmTileCoord c = gemm_tile_coord_impl(wg, tiles_m, tiles_n);
   *tm = c.tm;

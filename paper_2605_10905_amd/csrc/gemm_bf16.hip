@@ -21,6 +21,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "attn_device.h"
 #include "gemm_kernels.h"
 #include "gemm_map.h"
@@ -34,24 +36,28 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
   return __builtin_bit_cast(uint32_t, t);
 }
 
-template <int BK, int NSTAGE>
+// WM x WN 32x32 blocks per wave, 2 x 2 waves: the workgroup tile is 64 WM x 64 WN.
+template <int WM, int WN, int BK, int NSTAGE>
 struct GemmCfg {
-  static constexpr int BM = 256, BN = 256, NT = 256, NWAVES = 4;
+  static constexpr int BM = 64 * WM, BN = 64 * WN, NT = 256;
   static constexpr int ROWB = BK * 2, NCH = ROWB / 16;
-  static constexpr int TILEB = 256 * ROWB;          // one operand tile
-  static constexpr int STAGEB = 2 * TILEB;          // A tile then B tile
-  static constexpr int NLD = 256 * NCH / NT;        // direct-to-LDS loads per thread, tile and stage
+  static constexpr int TILEA = BM * ROWB, TILEB_ = BN * ROWB;
+  static constexpr int STAGEB = TILEA + TILEB_;  // A tile then B tile
+  static constexpr int NLDA = BM * NCH / NT, NLDB = BN * NCH / NT;  // direct-to-LDS loads per thread and stage
+  static constexpr int LPS = NLDA + NLDB;
   static constexpr int NKK = BK / 16;
+  static constexpr int LPP = LPS / NKK;  // loads issued per k-step
   static constexpr int LDS_BYTES = NSTAGE * STAGEB;
   static_assert(LDS_BYTES <= 160 * 1024, "ring does not fit the LDS");
-  static_assert((NSTAGE - 2) * 2 * NLD <= 63, "vmcnt field");
-  static_assert(NSTAGE >= 3 && (BK / 16) % 2 == 0, "pipeline shape");
+  static_assert((NSTAGE - 1) * LPS <= 63, "vmcnt field");
+  static_assert(NSTAGE >= 2 && NKK % 2 == 0 && LPS % NKK == 0 && NLDA >= 1 && NLDB >= 1, "pipeline shape");
 };
 
-template <int BK, int NSTAGE>
-__global__ void __launch_bounds__(256, 1) gemm_bf16_nt_kernel(const GemmParams p) {
-  using C = GemmCfg<BK, NSTAGE>;
-  constexpr int ROWB = C::ROWB, NCH = C::NCH, TILEB = C::TILEB, STAGEB = C::STAGEB, NLD = C::NLD, NKK = C::NKK;
+template <int WM, int WN, int BK, int NSTAGE, int MINW>
+__global__ void __launch_bounds__(256, MINW) gemm_bf16_nt_kernel(const GemmParams p) {
+  using C = GemmCfg<WM, WN, BK, NSTAGE>;
+  constexpr int ROWB = C::ROWB, NCH = C::NCH, TILEA = C::TILEA, STAGEB = C::STAGEB, NKK = C::NKK;
+  constexpr int NLDA = C::NLDA, NLDB = C::NLDB, LPS = C::LPS, LPP = C::LPP;
 
   __shared__ __attribute__((aligned(1024))) char smem_raw[C::LDS_BYTES];
   LDS_AS char* const smem = (LDS_AS char*)smem_raw;
@@ -68,114 +74,139 @@ __global__ void __launch_bounds__(256, 1) gemm_bf16_nt_kernel(const GemmParams p
 
   // ---- producer role: chunk s = it * 256 + tid of a tile is (row s / NCH, LDS chunk s % NCH) and
   // holds the row's chunk (s % NCH) ^ swizzle(row); rows past the matrix re-read its last row
-  uint32_t a_off[NLD], b_off[NLD];
+  uint32_t g_off[LPS];
 #pragma unroll
-  for (int it = 0; it < NLD; ++it) {
-    const int s = it * C::NT + tid;
+  for (int it = 0; it < LPS; ++it) {
+    const bool is_a = it < NLDA;
+    const int s = (is_a ? it : it - NLDA) * C::NT + tid;
     const int r = s / NCH, c = (s % NCH) ^ attn_swz_k<ROWB>(r);
-    a_off[it] = (uint32_t)(min(m0 + r, M - 1) - m0) * (uint32_t)rowbytes + c * 16;
-    b_off[it] = (uint32_t)(min(n0 + r, N - 1) - n0) * (uint32_t)rowbytes + c * 16;
+    const int row = is_a ? min(m0 + r, M - 1) - m0 : min(n0 + r, N - 1) - n0;
+    g_off[it] = (uint32_t)row * (uint32_t)rowbytes + c * 16;
   }
   const char* const a_tile = (const char*)p.a + (size_t)m0 * rowbytes;
   const char* const b_tile = (const char*)p.b + (size_t)n0 * rowbytes;
   const uint32_t lds_wave = (uint32_t)(uintptr_t)smem + w * 1024;
-  auto issue_stage = [&](int ks, int slot) __attribute__((always_inline)) {
-    const char* const ab = a_tile + (size_t)ks * ROWB;
-    const char* const bb = b_tile + (size_t)ks * ROWB;
-#pragma unroll
-    for (int it = 0; it < NLD; ++it) {
-      attn_lds_dma16(ab, a_off[it], lds_wave + slot * STAGEB + it * C::NT * 16);
-      attn_lds_dma16(bb, b_off[it], lds_wave + slot * STAGEB + TILEB + it * C::NT * 16);
-    }
+  // load `it` (0 .. LPS-1) of k-stage ks into ring slot `slot`
+  auto issue_load = [&](int ks, int slot, int it) __attribute__((always_inline)) {
+    if (it < NLDA) attn_lds_dma16(a_tile + (size_t)ks * ROWB, g_off[it], lds_wave + slot * STAGEB + it * C::NT * 16);
+    else attn_lds_dma16(b_tile + (size_t)ks * ROWB, g_off[it], lds_wave + slot * STAGEB + TILEA + (it - NLDA) * C::NT * 16);
   };
 
   const int nk = K / BK;
 #pragma unroll
-  for (int s = 0; s < NSTAGE - 1; ++s)
-    if (s < nk) issue_stage(s, s);
+  for (int s = 0; s < NSTAGE; ++s)
+    if (s < nk) {
+#pragma unroll
+      for (int it = 0; it < LPS; ++it) issue_load(s, s, it);
+    }
 
   // ---- consumer role: fragment addresses inside a stage (row block 0 of this wave's quarter)
   uint32_t ra[NKK], rb[NKK];
 #pragma unroll
   for (int kk = 0; kk < NKK; ++kk) {
-    const int rowa = wm * 128 + li, rowb = wn * 128 + li;
+    const int rowa = wm * 32 * WM + li, rowb = wn * 32 * WN + li;
     ra[kk] = rowa * ROWB + (((2 * kk + h) ^ attn_swz_k<ROWB>(rowa)) << 4);
-    rb[kk] = TILEB + rowb * ROWB + (((2 * kk + h) ^ attn_swz_k<ROWB>(rowb)) << 4);
+    rb[kk] = TILEA + rowb * ROWB + (((2 * kk + h) ^ attn_swz_k<ROWB>(rowb)) << 4);
   }
 
-  f32x16 acc[4][4];  // [n block][m block]: rows of the accumulator are n, its column is m
+  f32x16 acc[WN][WM];  // [n block][m block]: rows of the accumulator are n, its column is m
 #pragma unroll
-  for (int nb = 0; nb < 4; ++nb)
+  for (int nb = 0; nb < WN; ++nb)
 #pragma unroll
-    for (int mb = 0; mb < 4; ++mb)
+    for (int mb = 0; mb < WM; ++mb)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[nb][mb][r] = 0.f;
 
-  // Software pipeline inside the wave (it is alone on its SIMD): the fragments of k-step kk+1 are
-  // read while the 16 MFMAs of k-step kk run; the stage boundary (wait, barrier, refill of the
-  // slot that was consumed one stage ago, first fragments of the next stage) sits in front of the
-  // MFMAs of a stage's last k-step, so the matrix pipe has 16 MFMAs queued across it.
-  bf16x8 fa[2][4], fb[2][4];
+  // Software pipeline inside the wave: the fragments of k-step kk+1 are read while the MFMAs of
+  // k-step kk run.  The stage boundary (all fragments of stage ks are in registers: wait for
+  // stage ks+1, barrier, first fragments of stage ks+1) sits in front of the MFMAs of a stage's
+  // last k-step, so the matrix pipe has work queued across it; the slot of stage ks is free from
+  // that barrier on and is refilled with stage ks+NSTAGE, LPP loads per k-step, over the k-steps
+  // up to the next barrier.
+  bf16x8 fa[2][WM], fb[2][WN];
   auto read_frags = [&](int buf, int base, int kk) __attribute__((always_inline)) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      fa[buf][i] = *(LDS_AS bf16x8*)(smem + ra[kk] + base + i * 32 * ROWB);
-      fb[buf][i] = *(LDS_AS bf16x8*)(smem + rb[kk] + base + i * 32 * ROWB);
-    }
+    for (int i = 0; i < WM; ++i) fa[buf][i] = *(LDS_AS bf16x8*)(smem + ra[kk] + base + i * 32 * ROWB);
+#pragma unroll
+    for (int i = 0; i < WN; ++i) fb[buf][i] = *(LDS_AS bf16x8*)(smem + rb[kk] + base + i * 32 * ROWB);
   };
-  auto mfma16 = [&](int buf) __attribute__((always_inline)) {
+  auto mfmas = [&](int buf) __attribute__((always_inline)) {
 #pragma unroll
-    for (int nb = 0; nb < 4; ++nb)
+    for (int nb = 0; nb < WN; ++nb)
 #pragma unroll
-      for (int mb = 0; mb < 4; ++mb)
+      for (int mb = 0; mb < WM; ++mb)
         acc[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[buf][nb], fa[buf][mb], acc[nb][mb], 0, 0, 0);
   };
-  // 8 LDS reads spread over 16 MFMAs
+  // spread the WM + WN LDS reads of a k-step over its WM * WN MFMAs
   auto interleave = [&]() __attribute__((always_inline)) {
+    constexpr int NR = WM + WN, NM = WM * WN;
+    constexpr int PER = NM / NR > 0 ? NM / NR : 1;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
+    for (int i = 0; i < NR; ++i) {
       __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, PER, 0);
     }
   };
 
-  if (NSTAGE - 2 < nk) ATTN_WAIT_VMCNT((NSTAGE - 2) * 2 * NLD);
+  if (NSTAGE <= nk) ATTN_WAIT_VMCNT((NSTAGE - 1) * LPS);
   else ATTN_WAIT_VMCNT(0);
   attn_wg_barrier();
   read_frags(0, 0, 0);
 
-  int slot = 0;
-  for (int ks = 0; ks < nk; ++ks) {
+  // one k-stage; STEADY: every load and the next stage exist (no checks)
+  auto stage = [&](int ks, int slot, auto steady) __attribute__((always_inline)) {
+    constexpr bool STEADY = decltype(steady)::value;
     const int base = slot * STAGEB;
     const int nslot = slot == NSTAGE - 1 ? 0 : slot + 1;
+    const int pslot = slot == 0 ? NSTAGE - 1 : slot - 1;
 #pragma unroll
     for (int kk = 0; kk < NKK; ++kk) {
       const int cur = kk & 1, nxt = cur ^ 1;
       if (kk + 1 < NKK) {
         read_frags(nxt, base, kk + 1);
-      } else if (ks + 1 < nk) {
-        // stage ks+1 has landed once at most the NSTAGE-3 stages after it are outstanding
-        if (ks + NSTAGE - 2 < nk) ATTN_WAIT_VMCNT((NSTAGE - 3) * 2 * NLD);
+        if (STEADY || (ks >= 1 && ks - 1 + NSTAGE < nk)) {
+#pragma unroll
+          for (int i = 0; i < LPP; ++i) issue_load(ks - 1 + NSTAGE, pslot, (kk + 1) * LPP + i);
+        }
+      } else if (STEADY || ks + 1 < nk) {
+        __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): this wave's reads of the slot about to be refilled are done
+        if (STEADY || ks + NSTAGE - 1 < nk) ATTN_WAIT_VMCNT((NSTAGE - 2) * LPS);
         else ATTN_WAIT_VMCNT(0);
         attn_wg_barrier();
-        // every wave has finished stage ks-1: refill its slot
-        if (ks + NSTAGE - 1 < nk) issue_stage(ks + NSTAGE - 1, slot == 0 ? NSTAGE - 1 : slot - 1);
         read_frags(nxt, nslot * STAGEB, 0);
+        if (STEADY || ks + NSTAGE < nk) {
+#pragma unroll
+          for (int i = 0; i < LPP; ++i) issue_load(ks + NSTAGE, slot, i);
+        }
       }
-      mfma16(cur);
+      mfmas(cur);
       interleave();
     }
-    slot = nslot;
+  };
+
+  int slot = 0, ks = 0;
+  if (nk > 0) {
+    stage(0, 0, std::false_type{});
+    ks = 1;
+    slot = NSTAGE > 1 ? 1 : 0;
+  }
+  for (; ks + NSTAGE < nk; ++ks) {
+    stage(ks, slot, std::true_type{});
+    slot = slot == NSTAGE - 1 ? 0 : slot + 1;
+  }
+  for (; ks < nk; ++ks) {
+    stage(ks, slot, std::false_type{});
+    slot = slot == NSTAGE - 1 ? 0 : slot + 1;
   }
 
   // ---- epilogue: lane (li, h) holds, for row m, the columns n = 32 nb + 8 a + 4 h + (0..3) ---------
   const bool vec_ok = (N & 7) == 0;
 #pragma unroll
-  for (int mb = 0; mb < 4; ++mb) {
-    const int m = m0 + wm * 128 + mb * 32 + li;
+  for (int mb = 0; mb < WM; ++mb) {
+    const int m = m0 + wm * 32 * WM + mb * 32 + li;
     __bf16* const crow = (__bf16*)p.c + (size_t)min(m, M - 1) * N;
 #pragma unroll
-    for (int nb = 0; nb < 4; ++nb)
+    for (int nb = 0; nb < WN; ++nb)
 #pragma unroll
       for (int a = 0; a < 2; ++a) {
         uint32_t x[2], y[2];
@@ -187,7 +218,7 @@ __global__ void __launch_bounds__(256, 1) gemm_bf16_nt_kernel(const GemmParams p
           x[r] = sw[0];
           y[r] = sw[1];
         }
-        const int n = n0 + wn * 128 + nb * 32 + a * 16 + h * 8;  // this lane's 8 consecutive columns
+        const int n = n0 + wn * 32 * WN + nb * 32 + a * 16 + h * 8;  // this lane's 8 consecutive columns
         if (m < M) {
           if (vec_ok && n + 8 <= N) {
             u32x4 out = {x[0], x[1], y[0], y[1]};
@@ -203,9 +234,9 @@ __global__ void __launch_bounds__(256, 1) gemm_bf16_nt_kernel(const GemmParams p
   }
 }
 
-template <int BK, int NSTAGE>
+template <int WM, int WN, int BK, int NSTAGE, int MINW>
 int launch(const GemmParams& p, hipStream_t stream) {
-  hipLaunchKernelGGL((gemm_bf16_nt_kernel<BK, NSTAGE>), dim3(p.tiles_m * p.tiles_n), dim3(256), 0, stream, p);
+  hipLaunchKernelGGL((gemm_bf16_nt_kernel<WM, WN, BK, NSTAGE, MINW>), dim3(p.tiles_m * p.tiles_n), dim3(256), 0, stream, p);
   return (int)hipGetLastError();
 }
 
@@ -213,9 +244,12 @@ int launch(const GemmParams& p, hipStream_t stream) {
 
 const GemmVariant* gemm_bf16_nt_variants(int* count) {
   static const GemmVariant table[] = {
-      {"bf16 nt 256x256x32 ring4", 256, 256, 32, launch<32, 4>},
-      {"bf16 nt 256x256x32 ring5", 256, 256, 32, launch<32, 5>},
-      {"bf16 nt 256x256x32 ring3", 256, 256, 32, launch<32, 3>},
+      {"bf16 nt 256x256x32 ring4", 256, 256, 32, launch<4, 4, 32, 4, 1>},
+      {"bf16 nt 256x256x64 ring2", 256, 256, 64, launch<4, 4, 64, 2, 1>},
+      {"bf16 nt 128x128x64 ring2", 128, 128, 64, launch<2, 2, 64, 2, 2>},
+      {"bf16 nt 128x128x64 ring4", 128, 128, 64, launch<2, 2, 64, 4, 1>},
+      {"bf16 nt 64x64x64 ring2", 64, 64, 64, launch<1, 1, 64, 2, 4>},
+      {"bf16 nt 64x64x32 ring4", 64, 64, 32, launch<1, 1, 32, 4, 4>},
   };
   *count = (int)(sizeof(table) / sizeof(table[0]));
   return table;

@@ -109,3 +109,34 @@ def test_no_product_code_imports_the_oracle():
             if f.endswith((".py", ".hip", ".h", ".cpp")):
                 text = open(os.path.join(dirpath, f)).read()
                 assert "from oracle" not in text and "import oracle" not in text
+
+
+@pytest.mark.parametrize("M,N,tile", [(8192, 8192, 256), (2048, 2048, 128), (300, 5000, 64), (256, 256, 256), (1000, 777, 128),
+                                      (2304, 1024, 256)])
+def test_gemm_tile_map_is_a_bijection(A, M, N, tile):
+    n = A.gemm_num_workgroups(M, N, tile)
+    tm_n, tn_n = -(-M // tile), -(-N // tile)
+    assert n == tm_n * tn_n
+    seen = {A.gemm_tile_coord(wg, M, N, tile) for wg in range(n)}
+    assert seen == {(i, j) for i in range(tm_n) for j in range(tn_n)}
+    with pytest.raises(A.AttnError):
+        A.gemm_tile_coord(n, M, N, tile)
+
+
+def test_gemm_tile_map_keeps_an_xcd_on_few_rows(A):
+    """The 128 tiles an XCD owns of an 8192 x 8192 output (256-wide tiles) lie in one band of 4 tile rows."""
+    rows = {}
+    for wg in range(A.gemm_num_workgroups(8192, 8192, 256)):
+        tm, _ = A.gemm_tile_coord(wg, 8192, 8192, 256)
+        rows.setdefault(wg % 8, set()).add(tm)
+    assert all(len(r) == 4 for r in rows.values())
+
+
+def test_gemm_argument_validation_without_a_device(A):
+    p = 0x1000
+    assert A.gemm_bf16_nt(p, p, p, 64, 64, 48, stream=0, check=False) == 4
+    assert A.gemm_bf16_nt(None, p, p, 64, 64, 64, stream=0, check=False) == 1
+    assert A.gemm_bf16_nt(p, p, p, 64, -1, 64, stream=0, check=False) == 2
+    assert A.gemm_bf16_nt(p + 2, p, p, 64, 64, 64, stream=0, check=False) == 2
+    assert A.gemm_bf16_nt_variant(p, p, p, 64, 64, 64, 10 ** 6, stream=0, check=False) == 4
+    assert A.gemm_variant_tile(0) == 256 and A.gemm_variant_tile(-1) == 0
