@@ -79,6 +79,21 @@ int attn_fwd_fp8(const void* q, const void* k, const void* v, void* o, float* ls
                  float q_descale, float k_descale, float v_descale, void* stream);
 
 /*
+ * attn_fwd_persistent -- attn_fwd for bfloat16 as a persistent launch: one workgroup per compute
+ * unit, each taking query tiles from a queue in device memory until it is drained (the software
+ * form of the paper's dynamic tile assignment by cluster launch control, section 4.2: a kernel
+ * that stays resident and balances irregular tile run times).  Same results as attn_fwd.
+ *   queue   device, attn_persistent_queue_bytes() bytes, 128-byte aligned, owned by the caller;
+ *           contents on entry are irrelevant (the call enqueues a kernel that clears it first),
+ *           it must not be shared by calls that can overlap on the device
+ * Everything else as attn_fwd; dtype must be ATTN_BF16 (ATTN_ERR_UNSUPPORTED otherwise).
+ */
+int attn_fwd_persistent(const void* q, const void* k, const void* v, void* o, float* lse,
+                        int B, int Hq, int Hkv, int N, int d, int causal, float scale, int dtype,
+                        void* queue, void* stream);
+int attn_persistent_queue_bytes(void);
+
+/*
  * attn_bwd -- attention backward (the paper lists the backward pass beside the forward among
  * its attention kernels, section 6.1; appendix A, attention shape table, backward rows).
  * Gradients of attn_fwd with respect to q, k and v, given the gradient `dout` of o:

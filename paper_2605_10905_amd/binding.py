@@ -34,6 +34,10 @@ lib.attn_fwd_fp8.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _f
 lib.attn_fwd_fp8.restype = _i
 lib.attn_fwd_variant.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _f, _i, _i, _vp]
 lib.attn_fwd_variant.restype = _i
+lib.attn_fwd_persistent.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _f, _i, _vp, _vp]
+lib.attn_fwd_persistent.restype = _i
+lib.attn_persistent_queue_bytes.argtypes = []
+lib.attn_persistent_queue_bytes.restype = _i
 lib.attn_bwd.argtypes = [_vp] * 10 + [_i, _i, _i, _i, _i, _i, _f, _i, _vp]
 lib.attn_bwd.restype = _i
 lib.attn_bwd_workspace_bytes.argtypes = [_i, _i, _i]
@@ -195,3 +199,15 @@ def gemm_tile_coord(wg, M, N, tile):
     if st != 0:
         raise AttnError(st, "gemm_tile_coord")
     return tm.value, tn.value
+
+
+def attn_persistent_queue_bytes() -> int:
+    return lib.attn_persistent_queue_bytes()
+
+
+def attn_fwd_persistent(q, k, v, o, lse, B, Hq, Hkv, N, d, causal, scale, dtype, queue, stream=None, check=True):
+    st = lib.attn_fwd_persistent(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), B, Hq, Hkv, N, d, int(bool(causal)),
+                                 float(scale), int(dtype), _ptr(queue), _stream(stream))
+    if check and st != 0:
+        raise AttnError(st, "attn_fwd_persistent")
+    return st

@@ -121,6 +121,32 @@ int attn_fwd_variant(const void* q, const void* k, const void* v, void* o, float
   return run(q, k, v, o, lse, B, Hq, Hkv, N, d, causal, scale, dtype, 1.0f, 1.0f, variant, stream);
 }
 
+int attn_fwd_persistent(const void* q, const void* k, const void* v, void* o, float* lse, int B, int Hq, int Hkv, int N, int d,
+                        int causal, float scale, int dtype, void* queue, void* stream) {
+  int st = validate(q, k, v, o, lse, B, Hq, Hkv, N, d, scale, dtype);
+  if (st != ATTN_OK) return st;
+  if (!queue) return ATTN_ERR_NULL;
+  if (misaligned(queue, 128)) return ATTN_ERR_SHAPE;
+  if (dtype != ATTN_BF16) return ATTN_ERR_UNSUPPORTED;
+  AttnParams p;
+  p.q = q; p.k = k; p.v = v; p.o = o; p.lse = lse;
+  p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.N = N;
+  p.T = (N + 255) / 256;
+  p.causal = causal ? 1 : 0;
+  p.scale_log2 = scale * kLog2e;
+  p.out_scale = 1.0f;
+  const long long total = (long long)B * Hq * p.T;
+  if (total > 0x0fffffffll) return ATTN_ERR_UNSUPPORTED;
+  p.queue = (int*)queue;
+  p.total = (int)total;
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+    return ATTN_ERR_LAUNCH;
+  return attn_fwd_bf16_persistent_launch(p, d, cus, (hipStream_t)stream) == 0 ? ATTN_OK : ATTN_ERR_LAUNCH;
+}
+
+int attn_persistent_queue_bytes(void) { return 8 * 32 * (int)sizeof(int); }
+
 int attn_bwd(const void* q, const void* k, const void* v, const void* o, const void* dout, const float* lse, void* dq, void* dk,
              void* dv, float* workspace, int B, int Hq, int Hkv, int N, int d, int causal, float scale, int dtype, void* stream) {
   if (!q || !k || !v || !o || !dout || !lse || !dq || !dk || !dv || !workspace) return ATTN_ERR_NULL;

@@ -68,7 +68,14 @@ __device__ __forceinline__ void step_pipeline() {
   }
 }
 
-template <int D, bool CAUSAL>
+// PERSIST: the launch has one workgroup per CU, and each takes query tiles from a queue until
+// it is drained.  The queue is 8 counters, one per XCD list of the static tile order (a tile
+// index wg belongs to list wg % 8, the XCD the static launch would run it on, and lists are
+// consumed heaviest tile first); a workgroup serves the list of the XCD it was dispatched to
+// and, when that is empty, the lists after it, so every tile is taken exactly once whatever the
+// dispatch order was.  This is the software stand-in for the paper's cluster launch control
+// (section 4.2): dynamic assignment of tiles to resident workgroups.
+template <int D, bool CAUSAL, bool PERSIST>
 __global__ void __launch_bounds__(512, 2) attn_fwd_bf16_sp_kernel(const AttnParams p) {
   constexpr int BN = 64, NWAVES = 8, BM = NWAVES * 32, NT = NWAVES * 64;
   constexpr int NKK = D / 16;       // MFMA k-steps of S^T = K Q^T
@@ -93,13 +100,36 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_bf16_sp_kernel(const AttnPara
 
   __shared__ __attribute__((aligned(1024))) char smem_raw[2 * NSLOT * TILEB];
   LDS_AS char* const smem = (LDS_AS char*)smem_raw;
+  __shared__ int next_tile;
 
   const int tid = threadIdx.x;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const int qi = lane & 31;  // query column within the wave's 32-query block
   const int h = lane >> 5;   // which half of the k-slots / accumulator rows this lane holds
 
-  const AttnTileCoord tc = attn_tile_coord_impl(blockIdx.x, p.B, p.Hq, p.Hkv, p.T, CAUSAL ? 1 : 0);
+  int lists_tried = 0;  // used by thread 0 only
+  for (;;) {
+  int wg = blockIdx.x;
+  if constexpr (PERSIST) {
+    if (tid == 0) {
+      int t = -1;
+      while (lists_tried < 8) {
+        const int x = (blockIdx.x + lists_tried) & 7;
+        const int s = atomicAdd(p.queue + x * 32, 1);
+        if (s * 8 + x < p.total) {
+          t = s * 8 + x;
+          break;
+        }
+        ++lists_tried;  // that list is drained (its counter keeps growing, which is harmless)
+      }
+      next_tile = t;
+    }
+    __syncthreads();  // also: every wave is done with the LDS ring of the previous tile
+    wg = __builtin_amdgcn_readfirstlane(next_tile);
+    __syncthreads();
+    if (wg < 0) break;
+  }
+  const AttnTileCoord tc = attn_tile_coord_impl(wg, p.B, p.Hq, p.Hkv, p.T, CAUSAL ? 1 : 0);
   const int N = p.N;
   const int G = p.Hq / p.Hkv;
   const int hk = tc.hq / G;
@@ -464,16 +494,39 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_bf16_sp_kernel(const AttnPara
         }
       }
   }
+  if constexpr (!PERSIST) break;
+  }  // tile loop
 }
 
 template <int D>
 int launch_sp(const AttnParams& p, int grid, hipStream_t stream) {
-  if (p.causal) hipLaunchKernelGGL((attn_fwd_bf16_sp_kernel<D, true>), dim3(grid), dim3(512), 0, stream, p);
-  else hipLaunchKernelGGL((attn_fwd_bf16_sp_kernel<D, false>), dim3(grid), dim3(512), 0, stream, p);
+  if (p.causal) hipLaunchKernelGGL((attn_fwd_bf16_sp_kernel<D, true, false>), dim3(grid), dim3(512), 0, stream, p);
+  else hipLaunchKernelGGL((attn_fwd_bf16_sp_kernel<D, false, false>), dim3(grid), dim3(512), 0, stream, p);
   return (int)hipGetLastError();
 }
 
+// zero the 8 list counters (a kernel, not a memset, so that the pair can be captured in a graph)
+__global__ void attn_queue_reset_kernel(int* queue) {
+  if (threadIdx.x < 8) queue[threadIdx.x * 32] = 0;
+}
+
 }  // namespace
+
+int attn_fwd_bf16_persistent_launch(const AttnParams& p, int d, int workgroups, hipStream_t stream) {
+  if (!p.queue || p.total <= 0 || workgroups <= 0) return -1;
+  hipLaunchKernelGGL(attn_queue_reset_kernel, dim3(1), dim3(64), 0, stream, p.queue);
+  const dim3 grid(workgroups < p.total ? workgroups : p.total);
+  if (d == 128) {
+    if (p.causal) hipLaunchKernelGGL((attn_fwd_bf16_sp_kernel<128, true, true>), grid, dim3(512), 0, stream, p);
+    else hipLaunchKernelGGL((attn_fwd_bf16_sp_kernel<128, false, true>), grid, dim3(512), 0, stream, p);
+  } else if (d == 64) {
+    if (p.causal) hipLaunchKernelGGL((attn_fwd_bf16_sp_kernel<64, true, true>), grid, dim3(512), 0, stream, p);
+    else hipLaunchKernelGGL((attn_fwd_bf16_sp_kernel<64, false, true>), grid, dim3(512), 0, stream, p);
+  } else {
+    return -1;
+  }
+  return (int)hipGetLastError();
+}
 
 const AttnVariant* attn_bf16_sp_variants(int* count) {
   static const AttnVariant table[] = {

@@ -13,7 +13,12 @@ struct AttnParams {
   int causal;
   float scale_log2;  // scale * log2(e) (times q_descale*k_descale for fp8)
   float out_scale;   // multiplies O in the epilogue (v_descale and P scaling for fp8; 1 for bf16)
+  int* queue = nullptr;  // persistent launch only: 8 tile-list counters, 32 ints apart
+  int total = 0;         // persistent launch only: number of query tiles = B * Hq * T
 };
+
+// persistent bf16 forward (d = 64 or 128): `workgroups` resident workgroups drain the tile queue
+int attn_fwd_bf16_persistent_launch(const AttnParams& p, int d, int workgroups, hipStream_t stream);
 
 // backward pass (bf16, head dimension 128)
 struct AttnBwdParams {

@@ -214,3 +214,70 @@ def test_paper_grid_shapes_sampled(N, causal):
     if N <= 4096:
         mh = gu.check_whole_head(inp, o, lse, 0, heads[2][1], f"paper grid N={N} causal={causal}, whole head")
         print(f"paper grid N={N} causal={causal}: whole head {mh}", flush=True)
+
+
+# ---- persistent launch with the dynamic tile queue ------------------------------------------------
+def _run_persistent(inp, dev, queue_fill=0x7F):
+    import paper_2605_10905_amd as A
+
+    B, Hq, Hkv, N, d = inp["B"], inp["Hq"], inp["Hkv"], inp["N"], inp["d"]
+    o = torch.full((B, Hq, N, d), float("nan"), dtype=torch.bfloat16, device="cuda")
+    lse = torch.full((B, Hq, N), float("nan"), dtype=torch.float32, device="cuda")
+    # the queue's contents on entry must not matter
+    queue = torch.full((A.attn_persistent_queue_bytes(),), queue_fill, dtype=torch.uint8, device="cuda")
+    A.attn_fwd_persistent(dev["q"], dev["k"], dev["v"], o, lse, B, Hq, Hkv, N, d, inp["causal"], inp["scale"], A.ATTN_BF16, queue)
+    torch.cuda.synchronize()
+    return o, lse
+
+
+def _static_twin(d):
+    """Index of the kernel variant whose tile code the persistent launch runs."""
+    import paper_2605_10905_amd as A
+
+    return next(i for i in range(A.attn_num_variants()) if A.attn_variant_name(i) == f"bf16 d{d} pipelined BM256 BN64")
+
+
+@pytest.mark.parametrize("ci,B,Hq,Hkv,N", SMALL + [(1, 3, 5, 5, 700), (3, 2, 24, 3, 1300), (0, 2, 6, 3, 2100)])
+def test_persistent_reduced_configs(ci, B, Hq, Hkv, N):
+    cfg = wl.CONFIGS[ci]
+    inp = wl.make_inputs(cfg, B=B, Hq=Hq, Hkv=Hkv, N=N)
+    dev = gu.to_device(inp)
+    print(f"persistent config{ci + 1} reduced B={B} Hq={Hq} Hkv={Hkv} N={N}", flush=True)
+    o, lse = _run_persistent(inp, dev)
+    gu.check_full(inp, o, lse, f"persistent cfg{ci + 1} N={N}")
+    # every tile is computed by the same code as in the one-tile-per-workgroup launch of that kernel
+    o2, lse2 = gu.run_gpu(inp, dev, _static_twin(cfg["d"]))
+    assert torch.equal(o.view(torch.int16), o2.view(torch.int16)) and torch.equal(lse, lse2)
+
+
+@pytest.mark.parametrize("N", [1, 33, 255, 256, 257, 513])
+@pytest.mark.parametrize("causal", [False, True])
+def test_persistent_edge_lengths(N, causal):
+    cfg = dict(wl.CONFIGS[1], causal=causal, seed=277 + N)
+    inp = wl.make_inputs(cfg, B=1, Hq=2, Hkv=1, N=N)
+    print(f"persistent edge N={N} causal={causal}", flush=True)
+    o, lse = _run_persistent(inp, gu.to_device(inp))
+    gu.check_full(inp, o, lse, f"persistent edge N={N} causal={causal}")
+
+
+@pytest.mark.parametrize("ci", [1, 2, 3])
+def test_persistent_full_size_matches_static_launch(ci):
+    """Full-size configs (more tiles than workgroups, so the queue is exercised): the persistent
+    launch must reproduce the static launch bit for bit, whose parity the tests above cover."""
+    cfg = wl.CONFIGS[ci]
+    print(f"persistent full-size config{ci + 1}: generating inputs", flush=True)
+    inp = wl.make_inputs(cfg)
+    dev = gu.to_device(inp)
+    print(f"persistent full-size config{ci + 1}: launching", flush=True)
+    o, lse = _run_persistent(inp, dev)
+    o2, lse2 = gu.run_gpu(inp, dev, _static_twin(cfg["d"]))
+    assert torch.equal(o.view(torch.int16), o2.view(torch.int16)) and torch.equal(lse, lse2)
+    # twice in a row on the same queue buffer
+    import paper_2605_10905_amd as A
+    queue = torch.zeros(A.attn_persistent_queue_bytes(), dtype=torch.uint8, device="cuda")
+    B, Hq, Hkv, N, d = inp["B"], inp["Hq"], inp["Hkv"], inp["N"], inp["d"]
+    for _ in range(2):
+        o3 = torch.full_like(o, float("nan"))
+        A.attn_fwd_persistent(dev["q"], dev["k"], dev["v"], o3, lse, B, Hq, Hkv, N, d, inp["causal"], inp["scale"], A.ATTN_BF16, queue)
+        torch.cuda.synchronize()
+        assert torch.equal(o3.view(torch.int16), o2.view(torch.int16))
