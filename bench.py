@@ -119,6 +119,57 @@ def time_paper_grid(A, torch):
     return rows
 
 
+def time_persistent(A, torch, cfgs):
+    """Static launch (one workgroup per query tile) against the persistent launch with the tile
+    queue, same kernel code, interleaved in one process.  Inputs drawn on the device."""
+    import workloads as wl
+
+    rows = []
+    gen = torch.Generator(device="cuda")
+    for cfg in cfgs:
+        B, Hq, Hkv, N, d = cfg["B"], cfg["Hq"], cfg["Hkv"], cfg["N"], cfg["d"]
+        gen.manual_seed(cfg["seed"])
+        sig = cfg.get("sigma", 1.0)
+        q = (torch.randn((B, Hq, N, d), device="cuda", generator=gen) * sig).to(torch.bfloat16)
+        k, v = ((torch.randn((B, Hkv, N, d), device="cuda", generator=gen) * sig).to(torch.bfloat16) for _ in range(2))
+        o = torch.empty_like(q)
+        lse = torch.empty((B, Hq, N), dtype=torch.float32, device="cuda")
+        queue = torch.zeros(A.attn_persistent_queue_bytes(), dtype=torch.uint8, device="cuda")
+        stream = torch.cuda.current_stream()
+        twin = next(i for i in range(A.attn_num_variants()) if A.attn_variant_name(i) == f"bf16 d{d} pipelined BM256 BN64")
+
+        def static():
+            A.attn_fwd_variant(q, k, v, o, lse, B, Hq, Hkv, N, d, cfg["causal"], cfg["scale"], A.ATTN_BF16, twin, stream=stream)
+
+        def persistent():
+            A.attn_fwd_persistent(q, k, v, o, lse, B, Hq, Hkv, N, d, cfg["causal"], cfg["scale"], A.ATTN_BF16, queue, stream=stream)
+
+        flops = wl.algorithmic_flops(cfg)
+        est = flops / 1.0e15 + 5e-6
+        n = max(5, min(50, int(0.05 / est)))
+        res = {}
+        for _ in range(max(3, n)):
+            static()
+            persistent()
+        torch.cuda.synchronize()
+        for rep in range(2):
+            for name, fn in (("static", static), ("persistent", persistent)):
+                evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+                for a, b in evs:
+                    a.record(stream)
+                    fn()
+                    b.record(stream)
+                torch.cuda.synchronize()
+                res.setdefault(name, []).extend(a.elapsed_time(b) for a, b in evs)
+        ms_s, ms_p = float(np.median(res["static"])), float(np.median(res["persistent"]))
+        rows.append({"workload": cfg["name"], "static_ms": ms_s, "persistent_ms": ms_p,
+                     "static_TFLOP/s": flops / ms_s / 1e9, "persistent_TFLOP/s": flops / ms_p / 1e9})
+        log(f"[bench] {cfg['name']}: static {ms_s:.4f} ms ({flops / ms_s / 1e9:.1f} TFLOP/s)  persistent {ms_p:.4f} ms "
+            f"({flops / ms_p / 1e9:.1f} TFLOP/s)")
+        del q, k, v, o, lse
+    return rows
+
+
 def time_backward(A, torch, cfgs):
     """Backward pass (bf16, d = 128) on the given shapes: one step = attn_bwd (three kernels).
     Inputs are drawn on the device (seeded N(0,1), rounded to bf16) and O, lse come from
@@ -263,6 +314,9 @@ def main():
                     help="also time attn_bwd on the chosen config (with --all-configs: every bf16 d=128 config; with "
                          "--paper-grid: the paper's grid as well); "
                          "reported in 'backward'")
+    ap.add_argument("--persistent", action="store_true",
+                    help="also compare the persistent tile-queue launch with the static one on the bf16 configs (with "
+                         "--paper-grid: on the grid too); reported in 'persistent'")
     ap.add_argument("--gemm", action="store_true", help="also time the bf16 GEMM on the paper's shapes (reported in 'gemm')")
     ap.add_argument("--gemm-shape", default=None, help="with --gemm: only this shape (a name in workloads.GEMM_SHAPES)")
     ap.add_argument("--gemm-variants", action="store_true", help="with --gemm: time every kernel variant")
@@ -339,6 +393,11 @@ def main():
         if args.paper_grid:
             cfgs += wl.paper_grid()
         out["backward"] = time_backward(A, torch, cfgs)
+    if args.persistent:
+        cfgs = [c for c in wl.CONFIGS if c["dtype"] == "bf16"]
+        if args.paper_grid:
+            cfgs += wl.paper_grid()
+        out["persistent"] = time_persistent(A, torch, cfgs)
     if args.gemm:
         variants = [None] + list(range(A.gemm_num_variants())) if args.gemm_variants else [None]
         shapes = [g for g in wl.GEMM_SHAPES if args.gemm_shape in (None, g["name"])]
