@@ -280,8 +280,10 @@ __global__ void __launch_bounds__(512, 2) attn_bwd_dkv_kernel(const AttnBwdParam
   const int ki = lane & 31, h = lane >> 5;
 
   // one workgroup per (batch, kv head, key tile); all key tiles of a kv head share an XCD (they
-  // stream the same Q / dO); for causal inputs key tile 0 is the heaviest and goes first
-  const AttnTileCoord tc = attn_tile_coord_impl(blockIdx.x, p.B, p.Hkv, p.Hkv, p.T, 0);
+  // stream the same Q / dO); for causal inputs key tile 0 is the heaviest and goes first (the
+  // map's causal order, which issues its highest tile index first, read backwards)
+  AttnTileCoord tc = attn_tile_coord_impl(blockIdx.x, p.B, p.Hkv, p.Hkv, p.T, CAUSAL ? 1 : 0);
+  if (CAUSAL) tc.t = p.T - 1 - tc.t;
   const int N = p.N;
   const int G = p.Hq / p.Hkv;
   const int g = tc.hq;

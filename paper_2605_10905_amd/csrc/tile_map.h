@@ -21,20 +21,42 @@ struct AttnTileCoord {
   int b, hq, t;
 };
 
+// Causal launches with few tiles per K/V head are ordered tile-major inside batches of K/V heads
+// big enough to give every CU of an XCD about two workgroups (ATTN_CAUSAL_BATCH_WGS per XCD):
+// the heaviest tiles of the whole batch start first and its lightest fill the gaps, instead of
+// every head's light tiles being handed out before the next head's heavy ones.
+#ifndef ATTN_CAUSAL_BATCH_WGS
+#define ATTN_CAUSAL_BATCH_WGS 64
+#endif
+
 ATTN_HD inline AttnTileCoord attn_tile_coord_impl(int wg, int B, int Hq, int Hkv, int T, int causal) {
   const int G = Hq / Hkv;
   const int groups = B * Hkv;   // independent K/V heads
   const int W = G * T;          // workgroups that share one K/V head
-  int group, inner;
+  int xcd = 0, s = wg, lists = 1;
   if ((groups & 7) == 0) {
-    const int xcd = wg & 7, s = wg >> 3;
-    group = (s / W) * 8 + xcd;
-    inner = s % W;
-  } else {
-    group = wg / W;
-    inner = wg % W;
+    xcd = wg & 7;
+    s = wg >> 3;
+    lists = 8;
   }
-  const int tt = inner / G, hg = inner % G;
+  int gl, tt, hg;  // K/V head within this XCD's list, tile rank (0 = first issued), query head within the group
+  if (causal) {
+    const int gx = groups / lists;  // K/V heads in this list
+    const int per = (ATTN_CAUSAL_BATCH_WGS * (8 / lists) + W - 1) / W;  // K/V heads per batch
+    const int pb = per < gx ? per : gx;
+    const int batch = s / (pb * W), r = s % (pb * W);
+    const int nb = gx - batch * pb < pb ? gx - batch * pb : pb;  // the last batch may be short
+    tt = r / (nb * G);
+    const int rem = r % (nb * G);
+    gl = batch * pb + rem / G;
+    hg = rem % G;
+  } else {
+    gl = s / W;
+    const int inner = s % W;
+    tt = inner / G;
+    hg = inner % G;
+  }
+  const int group = gl * lists + xcd;
   AttnTileCoord c;
   c.b = group / Hkv;
   c.hq = (group % Hkv) * G + hg;

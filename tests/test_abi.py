@@ -77,7 +77,8 @@ def test_argument_validation_without_a_device(A):
 
 @pytest.mark.parametrize("B,Hq,Hkv,N,BM,causal", [
     (2, 32, 32, 8192, 256, 0), (4, 64, 8, 4096, 256, 1), (4, 16, 16, 2048, 256, 1), (1, 2, 2, 256, 128, 0),
-    (3, 6, 2, 1000, 128, 1), (1, 1, 1, 1, 256, 0),
+    (3, 6, 2, 1000, 128, 1), (1, 1, 1, 1, 256, 0), (4, 48, 48, 1024, 256, 1), (4, 48, 48, 2048, 256, 1), (4, 48, 48, 16384, 256, 1),
+    (5, 7, 7, 700, 256, 1), (2, 24, 4, 1300, 256, 1),
 ])
 def test_tile_map_is_a_bijection_and_xcd_local(A, B, Hq, Hkv, N, BM, causal):
     n = A.attn_num_workgroups(B, Hq, N, BM)
