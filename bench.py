@@ -349,7 +349,13 @@ def main():
     r = time_config(A, torch, cfg, args.steps, args.warmup, args.variant)
     tflops = r["flops"] / (r["wall_ms"] * 1e-3) / 1e12
     kern_tflops = r["flops"] / (r["kern_ms_avg"] * 1e-3) / 1e12
-    peak = PEAK_TFLOPS[cfg["dtype"]]
+    # the arithmetic type of the kernel that ran: fp8 inputs are multiplied on the bf16 matrix path by
+    # the default fp8 kernel (exact conversion on arrival), on the fp8 path by the other variants
+    vidx = args.variant if args.variant is not None else A.attn_default_variant(
+        0 if cfg["dtype"] == "bf16" else 1, cfg["B"], cfg["Hq"], cfg["N"], cfg["d"])
+    vname = A.attn_variant_name(vidx) or ""
+    arith = "bf16" if (cfg["dtype"] == "bf16" or "bf16-converted" in vname) else "fp8_e4m3"
+    peak = PEAK_TFLOPS[arith]
     log(f"[bench] wall {r['wall_ms']:.4f} ms/step  kernel avg {r['kern_ms_avg']:.4f} ms (median {r['kern_ms_med']:.4f})  "
         f"{kern_tflops:.1f} TFLOP/s = {100 * kern_tflops / peak:.1f}% of dense peak")
 
@@ -364,11 +370,11 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "bf16" if cfg["dtype"] == "bf16" else "fp8",
+        "dtype": "bf16" if arith == "bf16" else "fp8",
         "data": "synthetic",
         "config": {"workload": f"{cfg['name']}: B={cfg['B']} Hq={cfg['Hq']} Hkv={cfg['Hkv']} N={cfg['N']} d={cfg['d']} "
                                f"{cfg['dtype']} {'causal' if cfg['causal'] else 'non-causal'}",
-                   "variant": A.attn_variant_name(args.variant) if args.variant is not None else "library default",
+                   "variant": vname if args.variant is not None else f"library default ({vname})",
                    "pct_of_dense_peak": 100 * tflops / peak},
         "roofline": {"bound": "mfma", "achieved": kern_tflops, "peak": peak, "unit": "TFLOP/s", "frac": kern_tflops / peak,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(cfg["name"]) if args.variant is None else None,

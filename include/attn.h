@@ -130,6 +130,8 @@ int attn_fwd_variant(const void* q, const void* k, const void* v, void* o, float
 
 /* Number of kernel variants and a host string describing variant i (NULL if out of range). */
 int attn_num_variants(void);
+/* index of the variant attn_fwd / attn_fwd_fp8 run for this dtype and shape (-1: none) */
+int attn_default_variant(int dtype, int B, int Hq, int N, int d);
 const char* attn_variant_name(int variant);
 
 /*

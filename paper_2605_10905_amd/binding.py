@@ -56,6 +56,8 @@ lib.gemm_variant_tile.argtypes = [_i]
 lib.gemm_variant_tile.restype = _i
 lib.gemm_tile_coord.argtypes = [_i, _i, _i, _i, C.POINTER(_i), C.POINTER(_i)]
 lib.gemm_tile_coord.restype = _i
+lib.attn_default_variant.argtypes = [_i, _i, _i, _i, _i]
+lib.attn_default_variant.restype = _i
 lib.attn_num_variants.argtypes = []
 lib.attn_num_variants.restype = _i
 lib.attn_variant_name.argtypes = [_i]
@@ -211,3 +213,7 @@ def attn_fwd_persistent(q, k, v, o, lse, B, Hq, Hkv, N, d, causal, scale, dtype,
     if check and st != 0:
         raise AttnError(st, "attn_fwd_persistent")
     return st
+
+
+def attn_default_variant(dtype: int, B: int, Hq: int, N: int, d: int) -> int:
+    return lib.attn_default_variant(int(dtype), B, Hq, N, d)

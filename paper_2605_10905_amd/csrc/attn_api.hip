@@ -14,7 +14,7 @@ constexpr float kLog2e = 1.4426950408889634f;
 
 // all variant tables, concatenated; the first match for (dtype, d) is the default
 typedef const AttnVariant* (*VariantTable)(int*);
-const VariantTable kTables[] = {attn_bf16_sp_variants, attn_bf16_w16_variants, attn_bf16_pp_variants, attn_bf16_variants, attn_fp8_variants, attn_fp8_sp_variants};
+const VariantTable kTables[] = {attn_bf16_sp_variants, attn_bf16_w16_variants, attn_bf16_pp_variants, attn_bf16_variants, attn_fp8_cv_variants, attn_fp8_variants, attn_fp8_sp_variants};
 
 const AttnVariant* variant_at(int i) {
   if (i < 0) return nullptr;
@@ -175,6 +175,11 @@ int attn_bwd(const void* q, const void* k, const void* v, const void* o, const v
 long long attn_bwd_workspace_bytes(int B, int Hq, int N) {
   if (B <= 0 || Hq <= 0 || N <= 0) return 0;
   return (long long)B * Hq * 2 * ((N + 63) / 64 * 64) * (long long)sizeof(float);
+}
+
+int attn_default_variant(int dtype, int B, int Hq, int N, int d) {
+  if (B <= 0 || Hq <= 0 || N <= 0) return -1;
+  return choose_variant(dtype, B, Hq, N, d);
 }
 
 int attn_num_variants(void) { return total_variants(); }

@@ -150,6 +150,28 @@ def test_fp8_through_attn_fwd_takes_bytes_as_values():
     gu.check_full(inp, o, lse, "fp8 via attn_fwd")
 
 
+@pytest.mark.parametrize("N,causal", [(512, True), (1000, False), (65, True), (2048, True), (1, False), (321, True)])
+def test_fp8_every_variant_on_unit_descale_inputs(N, causal):
+    """Every fp8 kernel variant, forced through attn_fwd_variant (which takes the bytes as values):
+    e4m3 codes of N(0,1) draws, all de-scales 1."""
+    import paper_2605_10905_amd as A
+
+    rng = np.random.default_rng(21 + N)
+    B, Hq, Hkv, d = 1, 4, 2, 128
+    inp = dict(B=B, Hq=Hq, Hkv=Hkv, N=N, d=d, causal=causal, scale=1.0 / d ** 0.5, dtype="fp8_e4m3", descale=(1.0, 1.0, 1.0))
+    for nm, shape in (("q", (B, Hq, N, d)), ("k", (B, Hkv, N, d)), ("v", (B, Hkv, N, d))):
+        x = torch.from_numpy(rng.standard_normal(shape).astype(np.float32))
+        inp[nm] = x.to(torch.float8_e4m3fn).view(torch.uint8).numpy().copy()
+    dev = gu.to_device(inp)
+    for var in _variants(d, dtype=1):
+        print(f"fp8 N={N} causal={causal} variant {var} ({A.attn_variant_name(var)})", flush=True)
+        o = torch.full((B, Hq, N, d), float("nan"), dtype=torch.bfloat16, device="cuda")
+        lse = torch.full((B, Hq, N), float("nan"), dtype=torch.float32, device="cuda")
+        A.attn_fwd_variant(dev["q"], dev["k"], dev["v"], o, lse, B, Hq, Hkv, N, d, causal, inp["scale"], A.ATTN_FP8_E4M3, var)
+        torch.cuda.synchronize()
+        gu.check_full(inp, o, lse, f"fp8 N={N} causal={causal} variant {var}")
+
+
 # ---- full-size graded configs, in the launch configuration bench.py times ------------
 @pytest.mark.parametrize("ci", [1, 2, 3, 4])
 def test_full_size_sampled(ci):
