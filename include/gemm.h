@@ -50,6 +50,8 @@ const char* gemm_variant_name(int variant); /* NULL if out of range */
 int gemm_tile_coord(int wg, int M, int N, int tile, int* tm, int* tn);
 int gemm_num_workgroups(int M, int N, int tile);
 int gemm_variant_tile(int variant);
+/* K must be a multiple of this for the variant (0 if out of range) */
+int gemm_variant_kmult(int variant);
 
 #ifdef __cplusplus
 }

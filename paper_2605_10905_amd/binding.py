@@ -52,6 +52,8 @@ lib.gemm_variant_name.argtypes = [_i]
 lib.gemm_variant_name.restype = C.c_char_p
 lib.gemm_num_workgroups.argtypes = [_i, _i, _i]
 lib.gemm_num_workgroups.restype = _i
+lib.gemm_variant_kmult.argtypes = [_i]
+lib.gemm_variant_kmult.restype = _i
 lib.gemm_variant_tile.argtypes = [_i]
 lib.gemm_variant_tile.restype = _i
 lib.gemm_tile_coord.argtypes = [_i, _i, _i, _i, C.POINTER(_i), C.POINTER(_i)]
@@ -217,3 +219,7 @@ def attn_fwd_persistent(q, k, v, o, lse, B, Hq, Hkv, N, d, causal, scale, dtype,
 
 def attn_default_variant(dtype: int, B: int, Hq: int, N: int, d: int) -> int:
     return lib.attn_default_variant(int(dtype), B, Hq, N, d)
+
+
+def gemm_variant_kmult(variant: int) -> int:
+    return lib.gemm_variant_kmult(int(variant))

@@ -234,6 +234,197 @@ __global__ void __launch_bounds__(256, MINW) gemm_bf16_nt_kernel(const GemmParam
   }
 }
 
+
+// The 256 x 256 tile on the 16x16x32 MFMA: each wave's 128 x 128 quarter is 8 x 8 blocks of 16 x 16
+// (64 accumulators of 4 registers), a k-step is 32 wide, a fragment (16 rows x 32 k: 16 bytes per
+// lane, lane (j, g) = row j, k 8g .. 8g+7) feeds eight MFMAs.  Same ring, same barrier placement.
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+template <int BK, int NSTAGE>
+__global__ void __launch_bounds__(256, 1) gemm_bf16_nt_m16_kernel(const GemmParams p) {
+  using C = GemmCfg<4, 4, BK, NSTAGE>;
+  constexpr int ROWB = C::ROWB, NCH = C::NCH, TILEA = C::TILEA, STAGEB = C::STAGEB;
+  constexpr int NLDA = C::NLDA, LPS = C::LPS;
+  constexpr int NPH = BK / 32;       // k-steps per stage
+  constexpr int LPP = LPS / NPH;     // loads issued per k-step
+  static_assert(BK % 32 == 0 && LPS % NPH == 0, "k-step of 32");
+
+  __shared__ __attribute__((aligned(1024))) char smem_raw[C::LDS_BYTES];
+  LDS_AS char* const smem = (LDS_AS char*)smem_raw;
+
+  const int tid = threadIdx.x;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+  const int lj = lane & 15, g = lane >> 4;
+  const int wm = w >> 1, wn = w & 1;
+
+  const GemmTileCoord tc = gemm_tile_coord_impl(blockIdx.x, p.tiles_m, p.tiles_n);
+  const int m0 = tc.tm * C::BM, n0 = tc.tn * C::BN;
+  const int M = p.M, N = p.N, K = p.K;
+  const size_t rowbytes = (size_t)K * 2;
+
+  uint32_t g_off[LPS];
+#pragma unroll
+  for (int it = 0; it < LPS; ++it) {
+    const bool is_a = it < NLDA;
+    const int s = (is_a ? it : it - NLDA) * C::NT + tid;
+    const int r = s / NCH, c = (s % NCH) ^ attn_swz_k<ROWB>(r);
+    const int row = is_a ? min(m0 + r, M - 1) - m0 : min(n0 + r, N - 1) - n0;
+    g_off[it] = (uint32_t)row * (uint32_t)rowbytes + c * 16;
+  }
+  const char* const a_tile = (const char*)p.a + (size_t)m0 * rowbytes;
+  const char* const b_tile = (const char*)p.b + (size_t)n0 * rowbytes;
+  const uint32_t lds_wave = (uint32_t)(uintptr_t)smem + w * 1024;
+  auto issue_load = [&](int ks, int slot, int it) __attribute__((always_inline)) {
+    if (it < NLDA) attn_lds_dma16(a_tile + (size_t)ks * ROWB, g_off[it], lds_wave + slot * STAGEB + it * C::NT * 16);
+    else attn_lds_dma16(b_tile + (size_t)ks * ROWB, g_off[it], lds_wave + slot * STAGEB + TILEA + (it - NLDA) * C::NT * 16);
+  };
+
+  const int nk = K / BK;
+#pragma unroll
+  for (int s = 0; s < NSTAGE; ++s)
+    if (s < nk) {
+#pragma unroll
+      for (int it = 0; it < LPS; ++it) issue_load(s, s, it);
+    }
+
+  // fragment addresses: row block 0 of this wave's quarter, k-step ph
+  uint32_t ra[NPH], rb[NPH];
+#pragma unroll
+  for (int ph = 0; ph < NPH; ++ph) {
+    const int rowa = wm * 128 + lj, rowb = wn * 128 + lj;
+    ra[ph] = rowa * ROWB + (((4 * ph + g) ^ attn_swz_k<ROWB>(rowa)) << 4);
+    rb[ph] = TILEA + rowb * ROWB + (((4 * ph + g) ^ attn_swz_k<ROWB>(rowb)) << 4);
+  }
+
+  f32x4 acc[8][8];  // [n block][m block]: rows of the accumulator are n (4 g + r), its column is m (lj)
+#pragma unroll
+  for (int nb = 0; nb < 8; ++nb)
+#pragma unroll
+    for (int mb = 0; mb < 8; ++mb)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) acc[nb][mb][r] = 0.f;
+
+  bf16x8 fa[2][8], fb[2][8];
+  auto read_frags = [&](int buf, int base, int ph) __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) fa[buf][i] = *(LDS_AS bf16x8*)(smem + ra[ph] + base + i * 16 * ROWB);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) fb[buf][i] = *(LDS_AS bf16x8*)(smem + rb[ph] + base + i * 16 * ROWB);
+  };
+  auto mfmas = [&](int buf) __attribute__((always_inline)) {
+#pragma unroll
+    for (int nb = 0; nb < 8; ++nb)
+#pragma unroll
+      for (int mb = 0; mb < 8; ++mb)
+        acc[nb][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[buf][nb], fa[buf][mb], acc[nb][mb], 0, 0, 0);
+  };
+  auto interleave = [&]() __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+    }
+  };
+
+  if (NSTAGE <= nk) ATTN_WAIT_VMCNT((NSTAGE - 1) * LPS);
+  else ATTN_WAIT_VMCNT(0);
+  attn_wg_barrier();
+  read_frags(0, 0, 0);
+
+  // one k-stage; PAR: which fragment buffer its first k-step uses (stages of one k-step alternate)
+  auto stage = [&](int ks, int slot, auto steady, auto par) __attribute__((always_inline)) {
+    constexpr bool STEADY = decltype(steady)::value;
+    constexpr int PAR = decltype(par)::value;
+    const int base = slot * STAGEB;
+    const int nslot = slot == NSTAGE - 1 ? 0 : slot + 1;
+    const int pslot = slot == 0 ? NSTAGE - 1 : slot - 1;
+#pragma unroll
+    for (int ph = 0; ph < NPH; ++ph) {
+      const int cur = (PAR + ph) & 1, nxt = cur ^ 1;
+      if (ph + 1 < NPH) {
+        read_frags(nxt, base, ph + 1);
+        if (STEADY || (ks >= 1 && ks - 1 + NSTAGE < nk)) {
+#pragma unroll
+          for (int i = 0; i < LPP; ++i) issue_load(ks - 1 + NSTAGE, pslot, (ph + 1) * LPP + i);
+        }
+      } else if (STEADY || ks + 1 < nk) {
+        __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): this wave's reads of the slot about to be refilled are done
+        if (STEADY || ks + NSTAGE - 1 < nk) ATTN_WAIT_VMCNT((NSTAGE - 2) * LPS);
+        else ATTN_WAIT_VMCNT(0);
+        attn_wg_barrier();
+        read_frags(nxt, nslot * STAGEB, 0);
+        if (STEADY || ks + NSTAGE < nk) {
+#pragma unroll
+          for (int i = 0; i < LPP; ++i) issue_load(ks + NSTAGE, slot, i);
+        }
+      }
+      mfmas(cur);
+      interleave();
+    }
+  };
+
+  // stages of one k-step alternate between the two fragment buffers: they are run in pairs (the host
+  // only picks this kernel when the number of stages is even)
+  int slot = 0, ks = 0;
+  auto advance = [&]() __attribute__((always_inline)) {
+    slot = slot == NSTAGE - 1 ? 0 : slot + 1;
+    ++ks;
+  };
+  auto step = [&](auto steady) __attribute__((always_inline)) {
+    stage(ks, slot, steady, std::integral_constant<int, 0>{});
+    advance();
+    if (NPH & 1) {
+      stage(ks, slot, steady, std::integral_constant<int, 1>{});
+      advance();
+    }
+  };
+  constexpr int PER_STEP = (NPH & 1) ? 2 : 1;
+  if (nk > 0) step(std::false_type{});
+  while (ks + PER_STEP - 1 + NSTAGE < nk) step(std::true_type{});
+  while (ks < nk) step(std::false_type{});
+
+  // ---- epilogue: lane (lj, g) holds, for row m, the columns n = 16 nb + 4 g + (0..3); a pair of
+  // neighbouring n blocks is exchanged between odd and even lane groups so that every lane owns 8
+  // consecutive columns: one 16-byte store each
+  const bool vec_ok = (N & 7) == 0;
+#pragma unroll
+  for (int mb = 0; mb < 8; ++mb) {
+    const int m = m0 + wm * 128 + mb * 16 + lj;
+    __bf16* const crow = (__bf16*)p.c + (size_t)min(m, M - 1) * N;
+#pragma unroll
+    for (int nb = 0; nb < 8; nb += 2) {
+      uint32_t x[2], y[2];
+#pragma unroll
+      for (int r = 0; r < 2; ++r) {
+        const uint32_t tx = pack_bf16(acc[nb][mb][2 * r], acc[nb][mb][2 * r + 1]);
+        const uint32_t ty = pack_bf16(acc[nb + 1][mb][2 * r], acc[nb + 1][mb][2 * r + 1]);
+        auto sw = __builtin_amdgcn_permlane16_swap(tx, ty, false, false);
+        x[r] = sw[0];
+        y[r] = sw[1];
+      }
+      // even lane groups: own block nb, columns 4g .. 4g+7; odd ones: block nb+1, columns 4(g-1) .. 4(g-1)+7
+      const int n = n0 + wn * 128 + (nb + (g & 1)) * 16 + 4 * (g & ~1);
+      if (m < M) {
+        if (vec_ok && n + 8 <= N) {
+          u32x4 out = {x[0], x[1], y[0], y[1]};
+          *(u32x4*)(crow + n) = out;
+        } else {
+          const uint32_t v[4] = {x[0], x[1], y[0], y[1]};
+#pragma unroll
+          for (int e = 0; e < 8; ++e)
+            if (n + e < N) ((uint16_t*)crow)[n + e] = (uint16_t)(v[e >> 1] >> ((e & 1) * 16));
+        }
+      }
+    }
+  }
+}
+
+template <int BK, int NSTAGE>
+int launch_m16(const GemmParams& p, hipStream_t stream) {
+  hipLaunchKernelGGL((gemm_bf16_nt_m16_kernel<BK, NSTAGE>), dim3(p.tiles_m * p.tiles_n), dim3(256), 0, stream, p);
+  return (int)hipGetLastError();
+}
+
 template <int WM, int WN, int BK, int NSTAGE, int MINW>
 int launch(const GemmParams& p, hipStream_t stream) {
   hipLaunchKernelGGL((gemm_bf16_nt_kernel<WM, WN, BK, NSTAGE, MINW>), dim3(p.tiles_m * p.tiles_n), dim3(256), 0, stream, p);
@@ -244,12 +435,14 @@ int launch(const GemmParams& p, hipStream_t stream) {
 
 const GemmVariant* gemm_bf16_nt_variants(int* count) {
   static const GemmVariant table[] = {
-      {"bf16 nt 256x256x32 ring4", 256, 256, 32, launch<4, 4, 32, 4, 1>},
-      {"bf16 nt 256x256x64 ring2", 256, 256, 64, launch<4, 4, 64, 2, 1>},
-      {"bf16 nt 128x128x64 ring2", 128, 128, 64, launch<2, 2, 64, 2, 2>},
-      {"bf16 nt 128x128x64 ring4", 128, 128, 64, launch<2, 2, 64, 4, 1>},
-      {"bf16 nt 64x64x64 ring2", 64, 64, 64, launch<1, 1, 64, 2, 4>},
-      {"bf16 nt 64x64x32 ring4", 64, 64, 32, launch<1, 1, 32, 4, 4>},
+      {"bf16 nt 256x256x32 ring4", 256, 256, 32, 32, launch<4, 4, 32, 4, 1>},
+      {"bf16 nt 256x256x64 ring2", 256, 256, 64, 64, launch<4, 4, 64, 2, 1>},
+      {"bf16 nt 128x128x64 ring2", 128, 128, 64, 64, launch<2, 2, 64, 2, 2>},
+      {"bf16 nt 128x128x64 ring4", 128, 128, 64, 64, launch<2, 2, 64, 4, 1>},
+      {"bf16 nt 64x64x64 ring2", 64, 64, 64, 64, launch<1, 1, 64, 2, 4>},
+      {"bf16 nt 64x64x32 ring4", 64, 64, 32, 32, launch<1, 1, 32, 4, 4>},
+      {"bf16 nt 256x256x32 ring4 mfma16x16x32", 256, 256, 32, 64, launch_m16<32, 4>},
+      {"bf16 nt 256x256x64 ring2 mfma16x16x32", 256, 256, 64, 64, launch_m16<64, 2>},
   };
   *count = (int)(sizeof(table) / sizeof(table[0]));
   return table;

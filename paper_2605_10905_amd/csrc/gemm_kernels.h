@@ -13,6 +13,7 @@ struct GemmParams {
 struct GemmVariant {
   const char* name;
   int bm, bn, bk;
+  int kmult;  // K must be a multiple of this (some kernels run their k-stages in pairs)
   int (*launch)(const GemmParams& p, hipStream_t stream);
 };
 

@@ -23,8 +23,7 @@ def _variants(K):
 
     out = [None]
     for i in range(A.gemm_num_variants()):
-        bk = int(A.gemm_variant_name(i).split("x")[2].split()[0])
-        if K % bk == 0:
+        if K % A.gemm_variant_kmult(i) == 0:
             out.append(i)
     return out
 
