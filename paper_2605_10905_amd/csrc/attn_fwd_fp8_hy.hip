@@ -83,7 +83,10 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_fp8_hy_kernel(const AttnParam
   constexpr int NK8 = D / 64;           // f8f6f4 MFMA k-steps of S^T = K Q^T
   constexpr int VBASE = NSLOT * KTILEB; // fp8 K parts of the slots first, then the bf16 V parts
   constexpr int NLD = BN * NCH / NT;    // direct-to-LDS loads per thread per tile
-  constexpr int RA = 3;                 // operands are read from LDS this many MFMAs ahead
+#ifndef ATTN_HY_RA
+#define ATTN_HY_RA 4
+#endif
+  constexpr int RA = ATTN_HY_RA;        // operands are read from LDS this many MFMAs ahead
   static_assert(BN * NCH % NT == 0 && NLD >= 1, "tile must divide evenly over the workgroup");
   static_assert(NSLOT == 3 && NK8 == 2 && NCB == 4, "ring of three; the step below is written for d = 128");
 
