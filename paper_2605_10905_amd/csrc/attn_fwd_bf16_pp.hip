@@ -251,12 +251,6 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_bf16_pp_kernel(const AttnPara
 
   // VALU phase: mask, row max, (rare) rescale, P = exp2(c S - m_ref), row sum
   auto valu_phase = [&](int key0, bool need_mask) __attribute__((always_inline)) {
-#ifdef ATTN_EXP_SKIP_VALU
-    asm volatile("" ::"v"(s));  // the scores stay live, so the QK^T MFMAs are kept
-    pk[0] = u32x4{0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u}; pk[1] = pk[0]; l_run += 1.f; m_ref = 0.f;
-    asm volatile("" : "+v"(pk[0]), "+v"(pk[1]), "+v"(l_run));
-    return;
-#endif
     if (need_mask) {
       const int kbase = key0 + 4 * h;
 #pragma unroll
@@ -317,9 +311,6 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_bf16_pp_kernel(const AttnPara
   // the next block is one this wave never consumes, its S^T is computed on whatever the
   // LDS slot holds and then ignored.
   auto mfma_phase = [&](auto voff, auto koff) __attribute__((always_inline)) {
-#ifdef ATTN_EXP_SKIP_MFMA
-    return;
-#endif
 #pragma unroll
     for (int r = 0; r < 16; ++r) s[r] = 0.f;
     constexpr int NPV = NCB * 2;
@@ -358,10 +349,6 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_bf16_pp_kernel(const AttnPara
   // (independent accumulators, so neither waits for the other), then requests the operands of
   // step i + KP into the registers it has just freed.
   auto mfma_phase_ra = [&](auto voff, auto koff) __attribute__((always_inline)) {
-#ifdef ATTN_EXP_SKIP_MFMA
-    asm volatile("" : "+v"(s));
-    return;
-#endif
     static_assert(NKK == 2 * NCB && KP == NCB, "step pairing assumes D/16 QK steps and 2*D/32 PV steps");
 #pragma unroll
     for (int r = 0; r < 16; ++r) s[r] = 0.f;

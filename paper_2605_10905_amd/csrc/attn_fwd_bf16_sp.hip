@@ -156,9 +156,6 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_bf16_sp_kernel(const AttnPara
     ld_voff[it] = r * ROWB + ((c ^ attn_swz_v<ROWB>(r)) << 4);
   }
   auto issue_tile = [&](const char* head, int t, const uint32_t (&off)[NLD], uint32_t dst) __attribute__((always_inline)) {
-#ifdef ATTN_EXP_SKIP_DMA
-    if (t > 2) return;
-#endif
     const char* const base = head + (size_t)t * TILEB;
     if ((t + 1) * BN <= N) {
 #pragma unroll
@@ -212,15 +209,9 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_bf16_sp_kernel(const AttnPara
       }
   }
   auto k_operand = [&](auto koff, int kk) __attribute__((always_inline)) {
-#if defined(ATTN_EXP_SKIP_LDS) || defined(ATTN_EXP_SKIP_LDSK)
-    return u32x4{kaddr[kk], kaddr[kk], 0x3f803f80u, 0x3f803f80u};
-#endif
     return __builtin_bit_cast(u32x4, *(LDS_AS bf16x8*)(smem + kaddr[kk] + koff));
   };
   auto v_operand = [&](auto voff, int cb, int kc) __attribute__((always_inline)) {
-#if defined(ATTN_EXP_SKIP_LDS) || defined(ATTN_EXP_SKIP_LDSV)
-    return u32x4{vaddr[cb][0], vaddr[cb][1], 0x3f803f80u, 0x3f803f80u};
-#endif
     const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(smem + vaddr[cb][0] + voff + kc * 16 * ROWB));
     const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(smem + vaddr[cb][1] + voff + kc * 16 * ROWB));
     s16x8 av;
@@ -363,10 +354,6 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_bf16_sp_kernel(const AttnPara
       if (m + RA < NM) op[m + RA] = step_operand(off, m + RA);
       else pre[m + RA - NM] = step_operand(offnext, m + RA - NM);
     }
-#ifdef ATTN_EXP_SKIP_VALU
-    asm volatile("" ::"v"(s_in));
-    return;
-#endif
     float ls = exp_block(s_in, p_out);
     // pipeline: per MFMA one exponential, the plain vector work spread evenly, and the LDS
     // reads of the operand RA MFMAs ahead (one 128-bit K read or two transposing V reads)
@@ -427,9 +414,7 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_bf16_sp_kernel(const AttnPara
   auto bundle_mid = [&](int b, int free_slot) __attribute__((always_inline)) {
     if (NSLOT > 3 && b + 2 < nt) ATTN_WAIT_VMCNT(2 * NLD);  // bundle b+2 may stay in flight
     else ATTN_WAIT_VMCNT(0);
-#ifndef ATTN_EXP_NOBAR
     attn_wg_barrier();
-#endif
     if (b + NSLOT - 1 < nt) issue_bundle(b + NSLOT - 1, free_slot);
   };
   auto bundle_hot = [&](int b, auto slot_tag) __attribute__((always_inline)) {

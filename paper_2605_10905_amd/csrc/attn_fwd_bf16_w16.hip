@@ -194,15 +194,9 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_bf16_w16_kernel(const AttnPar
     }
   }
   auto k_operand = [&](auto koff, int kg, int kk) __attribute__((always_inline)) {
-#ifdef ATTN_EXP_SKIP_LDS
-    return u32x4{0x3c003c00u + kaddr[kk] * 0, 0x3c003c00u, 0x3c003c00u, 0x3c003c00u};
-#endif
     return __builtin_bit_cast(u32x4, *(LDS_AS bf16x8*)(smem + kaddr[kk] + koff + kg * 16 * ROWB));
   };
   auto v_operand = [&](auto voff, int dg) __attribute__((always_inline)) {
-#ifdef ATTN_EXP_SKIP_LDS
-    return u32x4{0x3c003c00u + vaddr[dg] * 0, 0x3c003c00u, 0x3c003c00u, 0x3c003c00u};
-#endif
     const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(smem + vaddr[dg] + voff));
     const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(smem + vaddr[dg] + voff + 16 * ROWB));
     s16x8 av;
@@ -357,13 +351,7 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_bf16_w16_kernel(const AttnPar
       }
     }
     float ls[2];
-#ifdef ATTN_EXP_SKIP_VALU
-    asm volatile("" ::"v"(s_in[0][0]), "v"(s_in[0][1]), "v"(s_in[1][0]), "v"(s_in[1][1]));
-    p_out[0] = p_out[1] = u32x4{0x3c003c00u, 0x3c003c00u, 0x3c003c00u, 0x3c003c00u};
-    ls[0] = ls[1] = 1.f;
-#else
     exp_block(s_in, p_out, ls);
-#endif
     // the packs belong to this step: keep the compiler from sinking them past the branch below
 #pragma unroll
     for (int qh = 0; qh < 2; ++qh)

@@ -201,15 +201,9 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_fp8_cv_kernel(const AttnParam
       }
   }
   auto k_operand = [&](auto koff, int kk) __attribute__((always_inline)) {
-#if defined(ATTN_EXP_SKIP_LDS) || defined(ATTN_EXP_SKIP_LDSK)
-    return u32x4{kaddr[kk], kaddr[kk], 0x3f803f80u, 0x3f803f80u};
-#endif
     return __builtin_bit_cast(u32x4, *(LDS_AS bf16x8*)(smem + kaddr[kk] + koff));
   };
   auto v_operand = [&](auto voff, int cb, int kc) __attribute__((always_inline)) {
-#if defined(ATTN_EXP_SKIP_LDS) || defined(ATTN_EXP_SKIP_LDSV)
-    return u32x4{vaddr[cb][0], vaddr[cb][1], 0x3f803f80u, 0x3f803f80u};
-#endif
     const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(smem + vaddr[cb][0] + voff + kc * 16 * ROWB));
     const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(smem + vaddr[cb][1] + voff + kc * 16 * ROWB));
     s16x8 av;
@@ -352,10 +346,6 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_fp8_cv_kernel(const AttnParam
       if (m + RA < NM) op[m + RA] = step_operand(off, m + RA);
       else pre[m + RA - NM] = step_operand(offnext, m + RA - NM);
     }
-#ifdef ATTN_EXP_SKIP_VALU
-    asm volatile("" ::"v"(s_in));
-    return;
-#endif
     float ls = exp_block(s_in, p_out);
     // pipeline: per MFMA one exponential, the plain vector work spread evenly, and the LDS
     // reads of the operand RA MFMAs ahead (one 128-bit K read or two transposing V reads)
