@@ -218,7 +218,13 @@ __global__ void __launch_bounds__(512, 2) attn_bwd_dq_kernel(const AttnBwdParams
       s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_operand(base, kk), qf[kk], s, 0, 0, 0);
       dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_operand(base + C::T2BASE, kk), dof[kk], dp, 0, 0, 0);
     }
-    const bool need_mask = (CAUSAL && key0 + 31 > wq0) || key0 + 31 >= N;
+    // invisible keys (causal diagonal, ragged tail): a score of -inf gives P = 0 and dS = 0.  The
+    // compare / select work sits behind a wave-uniform branch, the common case carries none of it.
+    if ((CAUSAL && key0 + 31 > wq0) || key0 + 31 >= N) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        if (key0 + 4 * h + 8 * (r >> 2) + (r & 3) > limit) s[r] = -INFINITY;
+    }
     u32x4 dsk[2];
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
@@ -226,8 +232,7 @@ __global__ void __launch_bounds__(512, 2) attn_bwd_dq_kernel(const AttnBwdParams
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
         const int r = 2 * u + t;
-        float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c, -lse2));
-        if (need_mask && key0 + 4 * h + 8 * (r >> 2) + (r & 3) > limit) pr = 0.f;
+        const float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c, -lse2));
         e[t] = pr * (dp[r] - delta);
       }
       dsk[u >> 2][u & 3] = pack_bf16(e[0], e[1]);
@@ -389,7 +394,13 @@ __global__ void __launch_bounds__(512, 2) attn_bwd_dkv_kernel(const AttnBwdParam
     }
     // accumulator row r of this lane is query q0b + 8 (r/4) + 4 h + r%4: its statistic and delta
     const LDS_AS float* const aux = (const LDS_AS float*)(smem + C::AUXBASE + slot * 512) + kb * 32 + 4 * h;
-    const bool need_mask = CAUSAL && q0b < wk0 + 31;  // some query of the block comes before some key of the wave
+    // some query of the block comes before some key of the wave: those scores become -inf (P = 0),
+    // behind a wave-uniform branch
+    if (CAUSAL && q0b < wk0 + 31) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        if (q0b + 8 * (r >> 2) + 4 * h + (r & 3) < krow) s[r] = -INFINITY;
+    }
     u32x4 pk[2];
 #pragma unroll
     for (int a = 0; a < 4; ++a) {
@@ -400,8 +411,7 @@ __global__ void __launch_bounds__(512, 2) attn_bwd_dkv_kernel(const AttnBwdParam
 #pragma unroll
       for (int t = 0; t < 4; ++t) {
         const int r = 4 * a + t;
-        float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c, -l4[t]));
-        if (need_mask && q0b + 8 * a + 4 * h + t < krow) pr = 0.f;
+        const float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c, -l4[t]));
         e[t] = WHICH ? pr * (dp[r] - d4[t]) : pr;
       }
       pk[a >> 1][2 * (a & 1)] = pack_bf16(e[0], e[1]);
