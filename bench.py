@@ -80,15 +80,15 @@ def time_config(A, torch, cfg, steps, warmup, variant=None):
                 kern_ms_med=float(np.median(kern_ms)), flops=flops)
 
 
-def time_paper_grid(A, torch):
-    """The paper's attention benchmark grid, bf16.  Inputs are drawn on the device (seeded
-    N(0,1), rounded to bf16): only their statistics matter for timing; parity on these shapes
-    is covered by the tests."""
+def time_paper_grid(A, torch, cfgs=None):
+    """The paper's attention benchmark grid (or the given shapes), bf16.  Inputs are drawn on the
+    device (seeded N(0,1), rounded to bf16): only their statistics matter for timing; parity on
+    these shapes is covered by the tests."""
     import workloads as wl
 
     rows = []
     gen = torch.Generator(device="cuda")
-    for cfg in wl.paper_grid():
+    for cfg in (wl.paper_grid() if cfgs is None else cfgs):
         B, H, N, d = cfg["B"], cfg["Hq"], cfg["N"], cfg["d"]
         gen.manual_seed(cfg["seed"])
         q, k, v = (torch.randn((B, H, N, d), device="cuda", generator=gen).to(torch.bfloat16) for _ in range(3))
@@ -314,6 +314,8 @@ def main():
                     help="also time attn_bwd on the chosen config (with --all-configs: every bf16 d=128 config; with "
                          "--paper-grid: the paper's grid as well); "
                          "reported in 'backward'")
+    ap.add_argument("--extra-shapes", action="store_true",
+                    help="also time head dimension 64 and ragged lengths at the headline size (reported in 'extra_shapes')")
     ap.add_argument("--persistent", action="store_true",
                     help="also compare the persistent tile-queue launch with the static one on the bf16 configs (with "
                          "--paper-grid: on the grid too); reported in 'persistent'")
@@ -396,6 +398,8 @@ def main():
         out["others"] = others
     if args.paper_grid:
         out["paper_grid"] = time_paper_grid(A, torch)
+    if args.extra_shapes:
+        out["extra_shapes"] = time_paper_grid(A, torch, wl.extra_shapes())
     if args.backward:
         cfgs = [c for c in wl.CONFIGS if c["dtype"] == "bf16" and c["d"] == 128 and (args.all_configs or c is cfg)]
         if args.paper_grid:

@@ -40,6 +40,18 @@ def paper_grid():
     return out
 
 
+def extra_shapes():
+    """Shapes beside the graded configs and the paper's grid: head dimension 64 and ragged lengths
+    (not multiples of the 64-key tile or the 256-query tile) at the headline size."""
+    out = []
+    for name, n, d, causal in (("d64_noncausal_8192", 8192, 64, False), ("d64_causal_8192", 8192, 64, True),
+                               ("ragged_noncausal_8191", 8191, 128, False), ("ragged_causal_8191", 8191, 128, True),
+                               ("ragged_noncausal_8000", 8000, 128, False), ("ragged_noncausal_1000", 1000, 128, False)):
+        out.append(dict(name=name, B=2, Hq=32, Hkv=32, N=n, d=d, dtype="bf16", sigma=1.0, causal=causal,
+                        scale=1.0 / math.sqrt(d), seed=2500 + n + d + int(causal)))
+    return out
+
+
 def algorithmic_flops(cfg) -> float:
     """4*B*Hq*N^2*d, halved for causal (the figure usually quoted for attention)."""
     f = 4.0 * cfg["B"] * cfg["Hq"] * cfg["N"] * cfg["N"] * cfg["d"]
