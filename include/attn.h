@@ -109,7 +109,7 @@ int attn_persistent_queue_bytes(void);
  *                 caller; contents on entry are irrelevant, contents on return unspecified
  *   dtype         ATTN_BF16 only; d must be 128 (ATTN_ERR_UNSUPPORTED otherwise)
  *
- * Deterministic (no atomics).  Three kernels are enqueued on `stream`; the call returns without
+ * Deterministic (no atomics).  Two kernels are enqueued on `stream`; the call returns without
  * synchronising.  Returns an attn_status; argument checks run before anything is enqueued.
  */
 int attn_bwd(const void* q, const void* k, const void* v, const void* o, const void* dout, const float* lse,

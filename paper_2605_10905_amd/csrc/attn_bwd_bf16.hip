@@ -8,21 +8,20 @@
 //     dV = P^T dO        dP = dO V^T        delta_i = sum_d dO_id O_id
 //     dS = P * (dP - delta)                 dQ = scale dS K        dK = scale dS^T Q
 //
-// Three kernels, none of which uses atomics or a reduction across workgroups, so the result is
-// deterministic and dQ needs no fp32 accumulation buffer in memory:
+// Two kernels, neither of which uses atomics or a reduction across workgroups, so the result is
+// deterministic and no gradient needs an fp32 accumulation buffer in memory:
 //
 //   * attn_bwd_dq_kernel: a workgroup owns 256 query rows (Q and dO rows stationary in registers
 //     as MFMA B operands, one query per lane, exactly the forward layout) and streams K/V tiles:
 //     S^T = K Q^T, dP^T = V dO^T, dS^T in registers, dQ^T += K^T dS^T.  It also writes the two
-//     per-row vectors the other kernels need, delta and lse * log2(e), into the workspace.
-//   * attn_bwd_dkv_kernel<.., 0>: a workgroup owns 256 keys (K rows stationary, one key per lane)
-//     and streams Q/dO tiles of every query head of its group: S = Q K^T, P, dV^T += dO^T P.
-//   * attn_bwd_dkv_kernel<.., 1>: the same with V rows stationary as well: dP = dO V^T,
-//     dS = P * (dP - delta), dK^T += Q^T dS.
-//   S (and dP) are therefore computed three (two) times, 8 matrix products per tile pair instead
-//   of the minimal 5: the price of keeping every accumulator in registers without atomics.
+//     per-row vectors the other kernel needs, delta and lse * log2(e), into the workspace.
+//   * attn_bwd_dkv_fused_kernel: a workgroup owns 128 keys (K and V rows stationary, one key per
+//     lane) and streams Q/dO tiles of every query head of its group: S = Q K^T, dP = dO V^T, P,
+//     dS = P * (dP - delta), dV^T += dO^T P, dK^T += Q^T dS.
+//   S and dP are therefore computed twice, 7 matrix products per tile pair instead of the minimal
+//   5: the price of keeping every accumulator in registers without atomics.
 //
-// All three share the forward kernels' machinery: 64-row tiles streamed HBM/L2 -> LDS by
+// Both share the forward kernels' machinery: 64-row tiles streamed HBM/L2 -> LDS by
 // direct-to-LDS loads into a three-slot ring two tiles ahead (one workgroup barrier per tile),
 // transposed products on the 32x32x16 MFMA so that the exponentiated accumulator is the next
 // B operand in place, and the transposing LDS read for the operand that must be contracted
@@ -269,11 +268,24 @@ __global__ void __launch_bounds__(512, 2) attn_bwd_dq_kernel(const AttnBwdParams
 }
 
 // =====================================================================================================
-// dV (WHICH = 0) and dK (WHICH = 1)
+// dK and dV in one kernel (S and dP computed once for both: 4 products per tile pair instead of the
+// 5 of the two separate kernels).  The accumulators of both gradients (128 registers per 32 keys)
+// beside the stationary K and V rows (64) leave no room for two waves per SIMD, so this kernel runs
+// four waves of 32 keys, one per SIMD, with the whole register file; a workgroup owns 128 keys.
 // =====================================================================================================
-template <bool CAUSAL, int WHICH>
-__global__ void __launch_bounds__(512, 2) attn_bwd_dkv_kernel(const AttnBwdParams p) {
-  using C = BwdCommon;
+struct BwdFused {
+  static constexpr int D = 128, BN = 64, NWAVES = 4, BM = NWAVES * 32, NT = NWAVES * 64;
+  static constexpr int NKK = D / 16, NCB = D / 32, ROWB = D * 2, NCH = ROWB / 16;
+  static constexpr int TILEB = BN * ROWB, SUBB = 32 * ROWB, NSLOT = 3;
+  static constexpr int T2BASE = NSLOT * TILEB;
+  static constexpr int AUXBASE = 2 * NSLOT * TILEB;
+  static constexpr int NLD = BN * NCH / NT;  // 4
+  static constexpr int LDS_BYTES = AUXBASE + NSLOT * 512;
+};
+
+template <bool CAUSAL>
+__global__ void __launch_bounds__(256, 1) attn_bwd_dkv_fused_kernel(const AttnBwdParams p) {
+  using C = BwdFused;
   constexpr int NKK = C::NKK, NCB = C::NCB, ROWB = C::ROWB, NCH = C::NCH, TILEB = C::TILEB, SUBB = C::SUBB, NSLOT = C::NSLOT;
   constexpr int NLD = C::NLD, NT = C::NT, BN = C::BN, BM = C::BM;
 
@@ -284,11 +296,9 @@ __global__ void __launch_bounds__(512, 2) attn_bwd_dkv_kernel(const AttnBwdParam
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const int ki = lane & 31, h = lane >> 5;
 
-  // one workgroup per (batch, kv head, key tile); all key tiles of a kv head share an XCD (they
-  // stream the same Q / dO); for causal inputs key tile 0 is the heaviest and goes first (the
-  // map's causal order, which issues its highest tile index first, read backwards)
-  AttnTileCoord tc = attn_tile_coord_impl(blockIdx.x, p.B, p.Hkv, p.Hkv, p.T, CAUSAL ? 1 : 0);
-  if (CAUSAL) tc.t = p.T - 1 - tc.t;
+  const int T128 = (p.N + BM - 1) / BM;
+  AttnTileCoord tc = attn_tile_coord_impl(blockIdx.x, p.B, p.Hkv, p.Hkv, T128, CAUSAL ? 1 : 0);
+  if (CAUSAL) tc.t = T128 - 1 - tc.t;  // key tile 0 is the heaviest: first
   const int N = p.N;
   const int G = p.Hq / p.Hkv;
   const int g = tc.hq;
@@ -298,13 +308,11 @@ __global__ void __launch_bounds__(512, 2) attn_bwd_dkv_kernel(const AttnBwdParam
   const int krow = wk0 + ki;
 
   const size_t koff = ((size_t)(tc.b * p.Hkv + g) * N) * ROWB;
-  // streamed range: query tiles qt0 .. nqt_all-1 of each of the G query heads of the group
   const int nqt_all = (N + BN - 1) / BN;
   const int qt0 = CAUSAL ? k0 / BN : 0;
   const int nqt = nqt_all - qt0;
   const int nt = G * nqt;
 
-  // ---- producer role ------------------------------------------------------------------------------
   int ld_row[NLD];
   uint32_t ld_off[NLD];
 #pragma unroll
@@ -327,15 +335,14 @@ __global__ void __launch_bounds__(512, 2) attn_bwd_dkv_kernel(const AttnBwdParam
       attn_lds_dma16(qb, ld_off[it] - over, lds_wave + slot * TILEB + it * NT * 16);
       attn_lds_dma16(db, ld_off[it] - over, lds_wave + C::T2BASE + slot * TILEB + it * NT * 16);
     }
-    // the tile's 64 statistics and 64 deltas: 32 lanes x 16 bytes, the same for every wave
     const float* const wsrow = p.ws + (size_t)(tc.b * p.Hq + hq) * 2 * p.Npad + (size_t)qt * BN;
     const uint32_t aoff = (uint32_t)(((lane & 15) * 4 + ((lane >> 4) & 1) * p.Npad) * 4);
     if (lane < 32) attn_lds_dma16(wsrow, aoff, lds_base + C::AUXBASE + slot * 512);
   };
+  constexpr int LPT = 2 * NLD + 1;  // loads per thread and tile
   issue_tile(0, 0);
 
-  // ---- stationary operands: K (and V) rows of this lane's key ----------------------------------------
-  bf16x8 kf[NKK], vf[WHICH ? NKK : 1];
+  bf16x8 kf[NKK], vf[NKK];
   {
     const int row = min(krow, N - 1);
     const char* ks = (const char*)p.k + koff + (size_t)row * ROWB + h * 16;
@@ -343,12 +350,11 @@ __global__ void __launch_bounds__(512, 2) attn_bwd_dkv_kernel(const AttnBwdParam
 #pragma unroll
     for (int kk = 0; kk < NKK; ++kk) {
       kf[kk] = *(const bf16x8*)(ks + kk * 32);
-      if constexpr (WHICH != 0) vf[kk] = *(const bf16x8*)(vs + kk * 32);
+      vf[kk] = *(const bf16x8*)(vs + kk * 32);
     }
   }
   if (nt > 1) issue_tile(1, 1);
 
-  // ---- LDS read addresses (slot 0, first 32-row block) --------------------------------------------
   uint32_t raddr[NKK];
 #pragma unroll
   for (int kk = 0; kk < NKK; ++kk) raddr[kk] = ki * ROWB + (((2 * kk + h) ^ swz_rt(ki)) << 4);
@@ -374,66 +380,67 @@ __global__ void __launch_bounds__(512, 2) attn_bwd_dkv_kernel(const AttnBwdParam
     return __builtin_bit_cast(bf16x8, av);
   };
 
-  f32x16 acc[NCB];  // dV^T or dK^T
+  f32x16 acc_dv[NCB], acc_dk[NCB];
 #pragma unroll
   for (int cb = 0; cb < NCB; ++cb)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) acc[cb][r] = 0.f;
+    for (int r = 0; r < 16; ++r) acc_dv[cb][r] = acc_dk[cb][r] = 0.f;
   const float c = p.scale_log2;
 
-  // one 32-query block of the tile in `slot`: q0b = first query row, base = byte offset inside the Q slots
-  auto block = [&](int q0b, int slot, int kb) __attribute__((always_inline)) {
-    const int base = slot * TILEB + kb * SUBB;
-    f32x16 s, dp;
+  auto scores = [&](f32x16& s, f32x16& dp, int base) __attribute__((always_inline)) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) s[r] = dp[r] = 0.f;
 #pragma unroll
     for (int kk = 0; kk < NKK; ++kk) {
       s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_operand(base, kk), kf[kk], s, 0, 0, 0);
-      if constexpr (WHICH != 0) dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_operand(base + C::T2BASE, kk), vf[kk], dp, 0, 0, 0);
+      dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_operand(base + C::T2BASE, kk), vf[kk], dp, 0, 0, 0);
     }
-    // accumulator row r of this lane is query q0b + 8 (r/4) + 4 h + r%4: its statistic and delta
-    const LDS_AS float* const aux = (const LDS_AS float*)(smem + C::AUXBASE + slot * 512) + kb * 32 + 4 * h;
-    // some query of the block comes before some key of the wave: those scores become -inf (P = 0),
-    // behind a wave-uniform branch
+  };
+  auto probs = [&](f32x16& s, const f32x16& dp, u32x4 (&pp)[2], u32x4 (&pd)[2], int q0b, int slot, int kb) __attribute__((always_inline)) {
     if (CAUSAL && q0b < wk0 + 31) {
 #pragma unroll
       for (int r = 0; r < 16; ++r)
         if (q0b + 8 * (r >> 2) + 4 * h + (r & 3) < krow) s[r] = -INFINITY;
     }
-    u32x4 pk[2];
+    const LDS_AS float* const aux = (const LDS_AS float*)(smem + C::AUXBASE + slot * 512) + kb * 32 + 4 * h;
 #pragma unroll
     for (int a = 0; a < 4; ++a) {
       const f32x4 l4 = *(const LDS_AS f32x4*)(aux + 8 * a);
-      f32x4 d4 = {0.f, 0.f, 0.f, 0.f};
-      if constexpr (WHICH != 0) d4 = *(const LDS_AS f32x4*)(aux + 64 + 8 * a);
-      float e[4];
+      const f32x4 d4 = *(const LDS_AS f32x4*)(aux + 64 + 8 * a);
+      float e[4], f[4];
 #pragma unroll
       for (int t = 0; t < 4; ++t) {
         const int r = 4 * a + t;
-        const float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c, -l4[t]));
-        e[t] = WHICH ? pr * (dp[r] - d4[t]) : pr;
+        e[t] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c, -l4[t]));
+        f[t] = e[t] * (dp[r] - d4[t]);
       }
-      pk[a >> 1][2 * (a & 1)] = pack_bf16(e[0], e[1]);
-      pk[a >> 1][2 * (a & 1) + 1] = pack_bf16(e[2], e[3]);
+      pp[a >> 1][2 * (a & 1)] = pack_bf16(e[0], e[1]);
+      pp[a >> 1][2 * (a & 1) + 1] = pack_bf16(e[2], e[3]);
+      pd[a >> 1][2 * (a & 1)] = pack_bf16(f[0], f[1]);
+      pd[a >> 1][2 * (a & 1) + 1] = pack_bf16(f[2], f[3]);
     }
-    // dV^T += dO^T P (transposed dO tile)   /   dK^T += Q^T dS (transposed Q tile)
-    const int tbase = WHICH ? base : base + C::T2BASE;
+  };
+  auto accumulate = [&](const u32x4 (&pp)[2], const u32x4 (&pd)[2], int base) __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < 2 * NCB; ++i) {
       const int cb = i % NCB, kc = i / NCB;
-      acc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_operand(tbase, cb, kc), __builtin_bit_cast(bf16x8, pk[kc]), acc[cb], 0, 0, 0);
+      acc_dv[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_operand(base + C::T2BASE, cb, kc), __builtin_bit_cast(bf16x8, pp[kc]), acc_dv[cb], 0, 0, 0);
+      acc_dk[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_operand(base, cb, kc), __builtin_bit_cast(bf16x8, pd[kc]), acc_dk[cb], 0, 0, 0);
     }
   };
+  auto block = [&](int q0b, int slot, int kb) __attribute__((always_inline)) {
+    const int base = slot * TILEB + kb * SUBB;
+    f32x16 s, dp;
+    u32x4 pp[2], pd[2];
+    scores(s, dp, base);
+    probs(s, dp, pp, pd, q0b, slot, kb);
+    accumulate(pp, pd, base);
+  };
 
-  if (nt > 1) ATTN_WAIT_VMCNT(2 * NLD + 1);
+  if (nt > 1) ATTN_WAIT_VMCNT(LPT);
   else ATTN_WAIT_VMCNT(0);
 #pragma unroll
-  for (int kk = 0; kk < NKK; ++kk) asm volatile("" ::"v"(kf[kk]));
-  if constexpr (WHICH != 0) {
-#pragma unroll
-    for (int kk = 0; kk < NKK; ++kk) asm volatile("" ::"v"(vf[kk]));
-  }
+  for (int kk = 0; kk < NKK; ++kk) asm volatile("" ::"v"(kf[kk]), "v"(vf[kk]));
   attn_wg_barrier();
 
   int slot = 0;
@@ -441,34 +448,35 @@ __global__ void __launch_bounds__(512, 2) attn_bwd_dkv_kernel(const AttnBwdParam
     const int pslot = slot == 0 ? NSLOT - 1 : slot - 1;
     if (j + 2 < nt) issue_tile(j + 2, pslot);
     const int qt = qt0 + j % nqt;
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
-      const int q0b = qt * BN + kb * 32;
-      // skip blocks past the end of Q and, for causal inputs, blocks whose queries all come before the wave's keys
-      if (wave_valid && q0b < N && (!CAUSAL || q0b + 31 >= wk0)) block(q0b, slot, kb);
+    {
+      const int q0b = qt * BN;
+      const bool act0 = wave_valid && q0b < N && (!CAUSAL || q0b + 31 >= wk0);
+      const bool act1 = wave_valid && q0b + 32 < N && (!CAUSAL || q0b + 63 >= wk0);
+      if (act0) block(q0b, slot, 0);
+      if (act1) block(q0b + 32, slot, 1);
     }
-    if (j + 2 < nt) ATTN_WAIT_VMCNT(2 * NLD + 1);
+    if (j + 2 < nt) ATTN_WAIT_VMCNT(LPT);
     else ATTN_WAIT_VMCNT(0);
     attn_wg_barrier();
     slot = slot == NSLOT - 1 ? 0 : slot + 1;
   }
 
-  char* const out = (char*)(WHICH ? p.dk : p.dv) + koff + (size_t)min(krow, N - 1) * ROWB;
-  store_transposed<NCB>(acc, WHICH ? p.scale : 1.0f, out, h, krow < N);
+  const size_t roff = koff + (size_t)min(krow, N - 1) * ROWB;
+  store_transposed<NCB>(acc_dv, 1.0f, (char*)p.dv + roff, h, krow < N);
+  store_transposed<NCB>(acc_dk, p.scale, (char*)p.dk + roff, h, krow < N);
 }
 
 }  // namespace
 
 int attn_bwd_launch_bf16_d128(const AttnBwdParams& p, hipStream_t stream) {
-  const int grid_q = p.B * p.Hq * p.T, grid_k = p.B * p.Hkv * p.T;
+  const int grid_q = p.B * p.Hq * p.T;
+  const int grid_f = p.B * p.Hkv * ((p.N + 127) / 128);
   if (p.causal) {
     hipLaunchKernelGGL((attn_bwd_dq_kernel<true>), dim3(grid_q), dim3(512), 0, stream, p);
-    hipLaunchKernelGGL((attn_bwd_dkv_kernel<true, 0>), dim3(grid_k), dim3(512), 0, stream, p);
-    hipLaunchKernelGGL((attn_bwd_dkv_kernel<true, 1>), dim3(grid_k), dim3(512), 0, stream, p);
+    hipLaunchKernelGGL((attn_bwd_dkv_fused_kernel<true>), dim3(grid_f), dim3(256), 0, stream, p);
   } else {
     hipLaunchKernelGGL((attn_bwd_dq_kernel<false>), dim3(grid_q), dim3(512), 0, stream, p);
-    hipLaunchKernelGGL((attn_bwd_dkv_kernel<false, 0>), dim3(grid_k), dim3(512), 0, stream, p);
-    hipLaunchKernelGGL((attn_bwd_dkv_kernel<false, 1>), dim3(grid_k), dim3(512), 0, stream, p);
+    hipLaunchKernelGGL((attn_bwd_dkv_fused_kernel<false>), dim3(grid_f), dim3(256), 0, stream, p);
   }
   return (int)hipGetLastError();
 }
