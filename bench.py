@@ -257,6 +257,27 @@ def time_gemm(A, torch, shapes, variants=(None,)):
                          "ms": ms, "TFLOP/s": tf, "pct_of_dense_peak": 100 * tf / PEAK_TFLOPS["bf16"]})
             log(f"[bench] gemm {g['name']} [{rows[-1]['variant']}]: {ms:.4f} ms  {tf:.1f} TFLOP/s = "
                 f"{100 * tf / PEAK_TFLOPS['bf16']:.1f}%")
+        if g["name"] in ("mi350_2048", "canonical_k4096", "canonical_k8192") and N % 8 == 0:
+            bkn = b.t().contiguous()  # the second operand stored [K, N]
+
+            def step_nn():
+                A.gemm_bf16_nn(a, bkn, c, M, N, K, stream=stream)
+
+            for _ in range(max(3, min(200, int(0.05 / est)))):
+                step_nn()
+            torch.cuda.synchronize()
+            evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+            for e0, e1 in evs:
+                e0.record(stream)
+                step_nn()
+                e1.record(stream)
+            torch.cuda.synchronize()
+            ms = float(np.median([e0.elapsed_time(e1) for e0, e1 in evs]))
+            tf = flops / (ms * 1e-3) / 1e12
+            rows.append({"workload": g["name"], "variant": "gemm_bf16_nn (B stored [K,N]), library default", "ms": ms, "TFLOP/s": tf,
+                         "pct_of_dense_peak": 100 * tf / PEAK_TFLOPS["bf16"]})
+            log(f"[bench] gemm {g['name']} [nn]: {ms:.4f} ms  {tf:.1f} TFLOP/s = {100 * tf / PEAK_TFLOPS['bf16']:.1f}%")
+            del bkn
         del a, b, c
     return rows
 

@@ -36,6 +36,15 @@ extern "C" {
  */
 int gemm_bf16_nt(const void* a, const void* b, void* c, int M, int N, int K, void* stream);
 
+/*
+ * gemm_bf16_nn -- C = A B with the second operand stored [K, N] row-major (N contiguous):
+ *     C[m, n] = sum_k A[m, k] * B[k, n]
+ * Arguments as for gemm_bf16_nt except b (device, bfloat16 [K, N]); N must be a multiple of 8
+ * (rows of B and C are moved in 16-byte pieces) and K a multiple of 32, ATTN_ERR_UNSUPPORTED
+ * otherwise.
+ */
+int gemm_bf16_nn(const void* a, const void* b, void* c, int M, int N, int K, void* stream);
+
 /* Tuning hook: the same with kernel variant `variant` (0 .. gemm_num_variants()-1);
  * ATTN_ERR_UNSUPPORTED if K is not a multiple of that variant's K-slice. */
 int gemm_bf16_nt_variant(const void* a, const void* b, void* c, int M, int N, int K, int variant, void* stream);

@@ -44,6 +44,8 @@ lib.attn_bwd_workspace_bytes.argtypes = [_i, _i, _i]
 lib.attn_bwd_workspace_bytes.restype = C.c_longlong
 lib.gemm_bf16_nt.argtypes = [_vp, _vp, _vp, _i, _i, _i, _vp]
 lib.gemm_bf16_nt.restype = _i
+lib.gemm_bf16_nn.argtypes = [_vp, _vp, _vp, _i, _i, _i, _vp]
+lib.gemm_bf16_nn.restype = _i
 lib.gemm_bf16_nt_variant.argtypes = [_vp, _vp, _vp, _i, _i, _i, _i, _vp]
 lib.gemm_bf16_nt_variant.restype = _i
 lib.gemm_num_variants.argtypes = []
@@ -223,3 +225,10 @@ def attn_default_variant(dtype: int, B: int, Hq: int, N: int, d: int) -> int:
 
 def gemm_variant_kmult(variant: int) -> int:
     return lib.gemm_variant_kmult(int(variant))
+
+
+def gemm_bf16_nn(a, b, c, M, N, K, stream=None, check=True):
+    st = lib.gemm_bf16_nn(_ptr(a), _ptr(b), _ptr(c), M, N, K, _stream(stream))
+    if check and st != 0:
+        raise AttnError(st, "gemm_bf16_nn")
+    return st

@@ -52,9 +52,32 @@ int run(const void* a, const void* b, void* c, int M, int N, int K, int variant,
   return v.launch(p, (hipStream_t)stream) == 0 ? ATTN_OK : ATTN_ERR_LAUNCH;
 }
 
+int run_nn(const void* a, const void* b, void* c, int M, int N, int K, void* stream) {
+  if (!a || !b || !c) return ATTN_ERR_NULL;
+  if (M <= 0 || N <= 0 || K <= 0) return ATTN_ERR_SHAPE;
+  if (misaligned(a, 16) || misaligned(b, 16) || misaligned(c, 16)) return ATTN_ERR_SHAPE;
+  if (K % 32 != 0 || N % 8 != 0) return ATTN_ERR_UNSUPPORTED;
+  if ((long long)K * 2 * 256 >= (1ll << 31) || (long long)N * 2 * 64 >= (1ll << 31)) return ATTN_ERR_UNSUPPORTED;
+  int count = 0;
+  const GemmVariant* table = gemm_bf16_nn_variants(&count);
+  const long long tiles256 = (long long)((M + 255) / 256) * ((N + 255) / 256);
+  const GemmVariant& v = table[tiles256 >= 200 ? 0 : 1];
+  GemmParams p;
+  p.a = a; p.b = b; p.c = c;
+  p.M = M; p.N = N; p.K = K;
+  p.tiles_m = (M + v.bm - 1) / v.bm;
+  p.tiles_n = (N + v.bn - 1) / v.bn;
+  if ((long long)p.tiles_m * p.tiles_n > 0x7fffffffll) return ATTN_ERR_UNSUPPORTED;
+  return v.launch(p, (hipStream_t)stream) == 0 ? ATTN_OK : ATTN_ERR_LAUNCH;
+}
+
 }  // namespace
 
 extern "C" {
+
+int gemm_bf16_nn(const void* a, const void* b, void* c, int M, int N, int K, void* stream) {
+  return run_nn(a, b, c, M, N, K, stream);
+}
 
 int gemm_bf16_nt(const void* a, const void* b, void* c, int M, int N, int K, void* stream) {
   return run(a, b, c, M, N, K, -1, stream);

@@ -53,9 +53,13 @@ struct GemmCfg {
   static_assert(NSTAGE >= 2 && NKK % 2 == 0 && LPS % NKK == 0 && NLDA >= 1 && NLDB >= 1, "pipeline shape");
 };
 
-template <int WM, int WN, int BK, int NSTAGE, int MINW>
-__global__ void __launch_bounds__(256, MINW) gemm_bf16_nt_kernel(const GemmParams p) {
+// BKN: the second operand is stored [K, N] (row-major, N contiguous) instead of [N, K].  Its tile is
+// then BK rows of BN columns in LDS, and the MFMA operand that needs 8 consecutive k per lane is
+// gathered with the transposing LDS read, exactly as the attention kernels read V.
+template <int WM, int WN, int BK, int NSTAGE, int MINW, bool BKN>
+__global__ void __launch_bounds__(256, MINW) gemm_bf16_kernel(const GemmParams p) {
   using C = GemmCfg<WM, WN, BK, NSTAGE>;
+  constexpr int ROWBB = C::BN * 2, NCHB = ROWBB / 16;  // [K,N] layout: bytes and 16-byte chunks per tile row
   constexpr int ROWB = C::ROWB, NCH = C::NCH, TILEA = C::TILEA, STAGEB = C::STAGEB, NKK = C::NKK;
   constexpr int NLDA = C::NLDA, NLDB = C::NLDB, LPS = C::LPS, LPP = C::LPP;
 
@@ -79,17 +83,27 @@ __global__ void __launch_bounds__(256, MINW) gemm_bf16_nt_kernel(const GemmParam
   for (int it = 0; it < LPS; ++it) {
     const bool is_a = it < NLDA;
     const int s = (is_a ? it : it - NLDA) * C::NT + tid;
-    const int r = s / NCH, c = (s % NCH) ^ attn_swz_k<ROWB>(r);
-    const int row = is_a ? min(m0 + r, M - 1) - m0 : min(n0 + r, N - 1) - n0;
-    g_off[it] = (uint32_t)row * (uint32_t)rowbytes + c * 16;
+    if (is_a || !BKN) {
+      const int r = s / NCH, c = (s % NCH) ^ attn_swz_k<ROWB>(r);
+      const int row = is_a ? min(m0 + r, M - 1) - m0 : min(n0 + r, N - 1) - n0;
+      g_off[it] = (uint32_t)row * (uint32_t)rowbytes + c * 16;
+    } else {
+      // [K,N] tile: k row r, LDS chunk s % NCHB holds the row's chunk XOR ((r & 3) << 2) (rows that the
+      // transposing read takes together land in different 64-byte groups); columns past N re-read
+      // the row's last 8 (N is a multiple of 8)
+      const int r = s / NCHB, c = (s % NCHB) ^ ((r & 3) << 2);
+      const int col = min(n0 + c * 8, N - 8) - n0;
+      g_off[it] = (uint32_t)r * (uint32_t)(N * 2) + col * 2;
+    }
   }
   const char* const a_tile = (const char*)p.a + (size_t)m0 * rowbytes;
-  const char* const b_tile = (const char*)p.b + (size_t)n0 * rowbytes;
+  const char* const b_tile = BKN ? (const char*)p.b + (size_t)n0 * 2 : (const char*)p.b + (size_t)n0 * rowbytes;
+  const size_t b_step = BKN ? (size_t)BK * N * 2 : (size_t)ROWB;  // bytes between consecutive k-stages of the second operand
   const uint32_t lds_wave = (uint32_t)(uintptr_t)smem + w * 1024;
   // load `it` (0 .. LPS-1) of k-stage ks into ring slot `slot`
   auto issue_load = [&](int ks, int slot, int it) __attribute__((always_inline)) {
     if (it < NLDA) attn_lds_dma16(a_tile + (size_t)ks * ROWB, g_off[it], lds_wave + slot * STAGEB + it * C::NT * 16);
-    else attn_lds_dma16(b_tile + (size_t)ks * ROWB, g_off[it], lds_wave + slot * STAGEB + TILEA + (it - NLDA) * C::NT * 16);
+    else attn_lds_dma16(b_tile + (size_t)ks * b_step, g_off[it], lds_wave + slot * STAGEB + TILEA + (it - NLDA) * C::NT * 16);
   };
 
   const int nk = K / BK;
@@ -107,6 +121,20 @@ __global__ void __launch_bounds__(256, MINW) gemm_bf16_nt_kernel(const GemmParam
     const int rowa = wm * 32 * WM + li, rowb = wn * 32 * WN + li;
     ra[kk] = rowa * ROWB + (((2 * kk + h) ^ attn_swz_k<ROWB>(rowa)) << 4);
     rb[kk] = TILEA + rowb * ROWB + (((2 * kk + h) ^ attn_swz_k<ROWB>(rowb)) << 4);
+  }
+  // [K,N] layout: in a group of 16 lanes, lane s reads four columns of k row s / 4 and the hardware
+  // hands lane t the four k of column t; read e of a fragment takes k = 8 h + 4 e + (0..3) of the k-step
+  uint32_t tb[WN][2];
+  {
+    const int s16 = lane & 15, chalf = (lane >> 4) & 1;
+#pragma unroll
+    for (int nb = 0; nb < WN; ++nb)
+#pragma unroll
+      for (int e = 0; e < 2; ++e) {
+        const int krow = 8 * h + 4 * e + (s16 >> 2);
+        const int chunk = (wn * 32 * WN + nb * 32) / 8 + chalf * 2 + ((s16 & 3) >> 1);
+        tb[nb][e] = TILEA + krow * ROWBB + ((chunk ^ ((krow & 3) << 2)) << 4) + ((s16 & 1) << 3);
+      }
   }
 
   f32x16 acc[WN][WM];  // [n block][m block]: rows of the accumulator are n, its column is m
@@ -127,8 +155,20 @@ __global__ void __launch_bounds__(256, MINW) gemm_bf16_nt_kernel(const GemmParam
   auto read_frags = [&](int buf, int base, int kk) __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < WM; ++i) fa[buf][i] = *(LDS_AS bf16x8*)(smem + ra[kk] + base + i * 32 * ROWB);
+    if constexpr (!BKN) {
 #pragma unroll
-    for (int i = 0; i < WN; ++i) fb[buf][i] = *(LDS_AS bf16x8*)(smem + rb[kk] + base + i * 32 * ROWB);
+      for (int i = 0; i < WN; ++i) fb[buf][i] = *(LDS_AS bf16x8*)(smem + rb[kk] + base + i * 32 * ROWB);
+    } else {
+#pragma unroll
+      for (int i = 0; i < WN; ++i) {
+        const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(smem + tb[i][0] + base + kk * 16 * ROWBB));
+        const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(smem + tb[i][1] + base + kk * 16 * ROWBB));
+        s16x8 av;
+        av[0] = v0[0]; av[1] = v0[1]; av[2] = v0[2]; av[3] = v0[3];
+        av[4] = v1[0]; av[5] = v1[1]; av[6] = v1[2]; av[7] = v1[3];
+        fb[buf][i] = __builtin_bit_cast(bf16x8, av);
+      }
+    }
   };
   auto mfmas = [&](int buf) __attribute__((always_inline)) {
 #pragma unroll
@@ -139,7 +179,7 @@ __global__ void __launch_bounds__(256, MINW) gemm_bf16_nt_kernel(const GemmParam
   };
   // spread the WM + WN LDS reads of a k-step over its WM * WN MFMAs
   auto interleave = [&]() __attribute__((always_inline)) {
-    constexpr int NR = WM + WN, NM = WM * WN;
+    constexpr int NR = WM + (BKN ? 2 * WN : WN), NM = WM * WN;
     constexpr int PER = NM / NR > 0 ? NM / NR : 1;
 #pragma unroll
     for (int i = 0; i < NR; ++i) {
@@ -425,9 +465,9 @@ int launch_m16(const GemmParams& p, hipStream_t stream) {
   return (int)hipGetLastError();
 }
 
-template <int WM, int WN, int BK, int NSTAGE, int MINW>
+template <int WM, int WN, int BK, int NSTAGE, int MINW, bool BKN = false>
 int launch(const GemmParams& p, hipStream_t stream) {
-  hipLaunchKernelGGL((gemm_bf16_nt_kernel<WM, WN, BK, NSTAGE, MINW>), dim3(p.tiles_m * p.tiles_n), dim3(256), 0, stream, p);
+  hipLaunchKernelGGL((gemm_bf16_kernel<WM, WN, BK, NSTAGE, MINW, BKN>), dim3(p.tiles_m * p.tiles_n), dim3(256), 0, stream, p);
   return (int)hipGetLastError();
 }
 
@@ -443,6 +483,15 @@ const GemmVariant* gemm_bf16_nt_variants(int* count) {
       {"bf16 nt 64x64x32 ring4", 64, 64, 32, 32, launch<1, 1, 32, 4, 4>},
       {"bf16 nt 256x256x32 ring4 mfma16x16x32", 256, 256, 32, 64, launch_m16<32, 4>},
       {"bf16 nt 256x256x64 ring2 mfma16x16x32", 256, 256, 64, 64, launch_m16<64, 2>},
+  };
+  *count = (int)(sizeof(table) / sizeof(table[0]));
+  return table;
+}
+
+const GemmVariant* gemm_bf16_nn_variants(int* count) {
+  static const GemmVariant table[] = {
+      {"bf16 nn 256x256x32 ring4", 256, 256, 32, 32, launch<4, 4, 32, 4, 1, true>},
+      {"bf16 nn 128x128x32 ring4", 128, 128, 32, 32, launch<2, 2, 32, 4, 2, true>},
   };
   *count = (int)(sizeof(table) / sizeof(table[0]));
   return table;

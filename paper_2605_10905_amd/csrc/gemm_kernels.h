@@ -4,7 +4,7 @@
 
 struct GemmParams {
   const void* a;  // bf16 [M, K]
-  const void* b;  // bf16 [N, K]
+  const void* b;  // bf16 [N, K] (nt kernels) or [K, N] (nn kernels)
   void* c;        // bf16 [M, N]
   int M, N, K;
   int tiles_m, tiles_n;
@@ -18,3 +18,4 @@ struct GemmVariant {
 };
 
 const GemmVariant* gemm_bf16_nt_variants(int* count);
+const GemmVariant* gemm_bf16_nn_variants(int* count);  // second operand stored [K, N]

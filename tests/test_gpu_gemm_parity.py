@@ -117,3 +117,47 @@ def test_gemm_full_size_sampled(name):
     rows = sorted({0, 1, 255, 256, 127, 128, M - 1, M // 2, *(int(r) for r in rng.integers(0, M, 24))} & set(range(M)))
     print(f"gemm full size {name}: oracle on {len(rows)} rows", flush=True)
     print(check(c, a, b, f"gemm {name}", rows=rows), flush=True)
+
+
+# ---- second operand stored [K, N] ---------------------------------------------------------------------
+def run_gemm_nn(a_bits, bkn_bits, poison=float("nan")):
+    import paper_2605_10905_amd as A
+
+    M, K = a_bits.shape
+    N = bkn_bits.shape[1]
+    a, b = gu.bf16_to_device(a_bits), gu.bf16_to_device(bkn_bits)
+    c = torch.full((M, N), poison, dtype=torch.bfloat16, device="cuda")
+    A.gemm_bf16_nn(a, b, c, M, N, K)
+    torch.cuda.synchronize()
+    return c
+
+
+@pytest.mark.parametrize("M,N,K", [(256, 256, 256), (300, 520, 96), (1, 8, 32), (257, 264, 1024), (1000, 72, 64), (33, 1000, 2048),
+                                   (777, 512, 160), (5, 8, 64), (2048, 2048, 512), (4096, 4352, 128)])
+def test_gemm_nn_shapes(M, N, K):
+    a, b = wl.make_gemm_inputs(700 + M + N + K, M, N, K)
+    bkn = np.ascontiguousarray(b.T)           # the same matrix stored [K, N]
+    print(f"gemm nn {M}x{N}x{K}", flush=True)
+    c = run_gemm_nn(a, bkn)
+    check(c, a, b, f"gemm nn {M}x{N}x{K}")   # the oracle on the [N, K] copy: same product
+    # and the oracle's own [K, N] path agrees with it
+    ref = og.gemm_ref(og.bf16_bits_to_f64(a), og.bf16_bits_to_f64(bkn), b_is_kn=True)
+    assert og.error_metrics(c.float().cpu().numpy().astype(np.float64), ref)["rel_fro"] <= 3e-3
+
+
+def test_gemm_nn_structured_and_unsupported():
+    import paper_2605_10905_amd as A
+
+    M, N, K = 384, 320, 128
+    rng = np.random.default_rng(4)
+    a = rng.standard_normal((M, K)).astype(np.float32)
+    bkn = np.zeros((K, N), dtype=np.float32)
+    rows = rng.integers(0, K, N)
+    bkn[rows, np.arange(N)] = 1.0              # column n of B selects column rows[n] of A
+    ab = wl.f32_to_bf16_bits(a)
+    c = run_gemm_nn(ab, wl.f32_to_bf16_bits(bkn))
+    want = torch.from_numpy(ab.view(np.int16)).view(torch.bfloat16)[:, torch.from_numpy(rows)]
+    assert torch.equal(c.cpu().view(torch.int16), want.contiguous().view(torch.int16))
+    t = torch.zeros(64 * 64, dtype=torch.bfloat16, device="cuda")
+    assert A.gemm_bf16_nn(t, t, t, 64, 60, 32, check=False) != 0   # N not a multiple of 8
+    assert A.gemm_bf16_nn(t, t, t, 64, 64, 24, check=False) != 0   # K not a multiple of 32
