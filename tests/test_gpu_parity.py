@@ -303,3 +303,57 @@ def test_persistent_full_size_matches_static_launch(ci):
         A.attn_fwd_persistent(dev["q"], dev["k"], dev["v"], o3, lse, B, Hq, Hkv, N, d, inp["causal"], inp["scale"], A.ATTN_BF16, queue)
         torch.cuda.synchronize()
         assert torch.equal(o3.view(torch.int16), o2.view(torch.int16))
+
+
+# ---- stream capture: nothing in the library allocates, synchronises or uses a memset node --------------
+def test_calls_can_be_captured_in_a_graph_and_replayed():
+    """attn_fwd, attn_fwd_persistent (whose queue is cleared by a kernel) and attn_bwd captured into
+    one graph; every replay, with eager work in between, must reproduce the eager results."""
+    import paper_2605_10905_amd as A
+
+    cfg = wl.CONFIGS[3]
+    inp = wl.make_inputs(cfg, B=1, Hq=8, Hkv=2, N=1300)
+    dob = wl.make_dout(cfg, B=1, Hq=8, N=1300)
+    dev = gu.to_device(inp)
+    do = gu.bf16_to_device(dob)
+    B, Hq, Hkv, N, d = inp["B"], inp["Hq"], inp["Hkv"], inp["N"], inp["d"]
+    args = (B, Hq, Hkv, N, d, inp["causal"], inp["scale"], A.ATTN_BF16)
+
+    def buffers():
+        return dict(o=torch.zeros((B, Hq, N, d), dtype=torch.bfloat16, device="cuda"),
+                    lse=torch.zeros((B, Hq, N), dtype=torch.float32, device="cuda"),
+                    o2=torch.zeros((B, Hq, N, d), dtype=torch.bfloat16, device="cuda"),
+                    lse2=torch.zeros((B, Hq, N), dtype=torch.float32, device="cuda"),
+                    dq=torch.zeros((B, Hq, N, d), dtype=torch.bfloat16, device="cuda"),
+                    dk=torch.zeros((B, Hkv, N, d), dtype=torch.bfloat16, device="cuda"),
+                    dv=torch.zeros((B, Hkv, N, d), dtype=torch.bfloat16, device="cuda"),
+                    ws=torch.zeros(A.attn_bwd_workspace_bytes(B, Hq, N) // 4, dtype=torch.float32, device="cuda"),
+                    queue=torch.zeros(A.attn_persistent_queue_bytes(), dtype=torch.uint8, device="cuda"))
+
+    def run(t):
+        A.attn_fwd(dev["q"], dev["k"], dev["v"], t["o"], t["lse"], *args)
+        A.attn_fwd_persistent(dev["q"], dev["k"], dev["v"], t["o2"], t["lse2"], *args, t["queue"])
+        A.attn_bwd(dev["q"], dev["k"], dev["v"], t["o"], do, t["lse"], t["dq"], t["dk"], t["dv"], t["ws"], *args)
+
+    eager = buffers()
+    run(eager)
+    torch.cuda.synchronize()
+
+    cap = buffers()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run(cap)  # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        run(cap)
+    for rep in range(3):
+        for name in ("o", "lse", "o2", "lse2", "dq", "dk", "dv"):
+            cap[name].fill_(7.0)  # eager work between the replays; also proves the replay rewrites everything
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for name in ("o", "lse", "o2", "lse2", "dq", "dk", "dv"):
+            assert torch.equal(cap[name].view(torch.uint8), eager[name].view(torch.uint8)), f"replay {rep}: {name} differs"
