@@ -54,27 +54,16 @@ int validate(const void* q, const void* k, const void* v, void* o, float* lse, i
   return ATTN_OK;
 }
 
-// Default choice: the widest query tile for long sequences (fewest K/V re-reads per
-// query row), the 128-row tile when the launch would otherwise not fill the chip.
+// Default choice: the first listed variant for (dtype, d).  The smaller query tiles of the first
+// kernel do not pay even when the launch leaves CUs idle: the pipelined kernel on half the chip
+// still beats them (e.g. 128 workgroups at N = 8192: 160 against 228 microseconds).
 int choose_variant(int dtype, int B, int Hq, int N, int d) {
-  int best = -1;
+  (void)B; (void)Hq; (void)N;
   for (int i = 0; i < total_variants(); ++i) {
     const AttnVariant* a = variant_at(i);
-    if (a->dtype != dtype || a->d != d) continue;
-    if (best < 0) { best = i; continue; }
+    if (a->dtype == dtype && a->d == d) return i;
   }
-  if (best < 0) return -1;
-  // first listed variant for (dtype,d) is the default; fall back to a smaller tile if
-  // the grid would leave most of the 256 CUs idle
-  const AttnVariant* a = variant_at(best);
-  long long wgs = (long long)B * Hq * ((N + a->bm - 1) / a->bm);
-  if (wgs < 256) {
-    for (int i = 0; i < total_variants(); ++i) {
-      const AttnVariant* c = variant_at(i);
-      if (c->dtype == dtype && c->d == d && c->bm < a->bm && c->threads <= 256) { best = i; break; }
-    }
-  }
-  return best;
+  return -1;
 }
 
 int run(const void* q, const void* k, const void* v, void* o, float* lse, int B, int Hq, int Hkv, int N, int d, int causal,
