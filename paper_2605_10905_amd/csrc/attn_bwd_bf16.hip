@@ -466,6 +466,288 @@ __global__ void __launch_bounds__(256, 1) attn_bwd_dkv_fused_kernel(const AttnBw
   store_transposed<NCB>(acc_dk, p.scale, (char*)p.dk + roff, h, krow < N);
 }
 
+
+// =====================================================================================================
+// The same kernel software-pipelined inside the wave.  With one wave per SIMD nothing else hides the
+// vector work of a block behind matrix work, so a step works on three blocks at once: the score
+// products of block i+1, the exponentials and dS of block i, and the gradient products of block
+// i-1.  The 32 MFMAs of a step depend on none of its vector work.  Instruction order inside a step is
+// fixed by hand (one MFMA per slot, operands read RA slots ahead, the vector work of one row per
+// slot) and fenced slot by slot; the ring has four slots because a step touches three tiles.
+// Every block of every tile is computed by every wave: a block that is invisible to the wave's keys
+// (causal) or past the end (ragged) contributes exact zeros through the -inf scores and the +inf
+// statistic of the padded workspace rows, and the slowest wave of the workgroup computes it anyway.
+// =====================================================================================================
+#ifndef ATTN_BWD_RA
+#define ATTN_BWD_RA 6
+#endif
+struct BwdPipe {
+  static constexpr int D = 128, BN = 64, NWAVES = 4, BM = NWAVES * 32, NT = NWAVES * 64;
+  static constexpr int NKK = D / 16, NCB = D / 32, ROWB = D * 2, NCH = ROWB / 16;
+  static constexpr int TILEB = BN * ROWB, SUBB = 32 * ROWB, NSLOT = 4;
+  static constexpr int T2BASE = NSLOT * TILEB;
+  static constexpr int AUXBASE = 2 * NSLOT * TILEB;
+  static constexpr int NLD = BN * NCH / NT;  // 4
+  static constexpr int LDS_BYTES = AUXBASE + NSLOT * 512;
+  static constexpr int NM = 32, RA = ATTN_BWD_RA;
+  // slot p of a step: the first RA MFMAs are gradient products (their operands were requested by
+  // the previous step, from a tile that is certainly resident), then score and gradient products
+  // alternate, and the last RA are score products
+  static constexpr bool is_score(int p) {
+    if (p < RA) return false;
+    const int q = p - RA, npairs = 16 - RA;
+    return q < 2 * npairs ? (q & 1) == 0 : true;
+  }
+  static constexpr int index(int p) {
+    if (p < RA) return p;
+    const int q = p - RA, npairs = 16 - RA;
+    if (q < 2 * npairs) return (q & 1) == 0 ? q / 2 : RA + q / 2;
+    return npairs + (q - 2 * npairs);
+  }
+  static constexpr int VP0 = 6;                                                       // first slot with vector work
+  static constexpr int vslot(int r) { return VP0 + (r * (NM - VP0)) / 16; }            // slot of row r's vector work
+  static constexpr int aslot(int a) { return vslot(4 * a) - 6 > 0 ? vslot(4 * a) - 6 : 0; }  // slot that reads the statistics of rows 4a..4a+3
+};
+
+template <bool CAUSAL>
+__global__ void __launch_bounds__(256, 1) attn_bwd_dkv_pipe_kernel(const AttnBwdParams p) {
+  using C = BwdPipe;
+  constexpr int NKK = C::NKK, NCB = C::NCB, ROWB = C::ROWB, NCH = C::NCH, TILEB = C::TILEB, SUBB = C::SUBB, NSLOT = C::NSLOT;
+  constexpr int NLD = C::NLD, NT = C::NT, BN = C::BN, BM = C::BM, NM = C::NM, RA = C::RA;
+
+  __shared__ __attribute__((aligned(1024))) char smem_raw[C::LDS_BYTES];
+  LDS_AS char* const smem = (LDS_AS char*)smem_raw;
+
+  const int tid = threadIdx.x;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+  const int ki = lane & 31, h = lane >> 5;
+
+  const int T128 = (p.N + BM - 1) / BM;
+  AttnTileCoord tc = attn_tile_coord_impl(blockIdx.x, p.B, p.Hkv, p.Hkv, T128, CAUSAL ? 1 : 0);
+  if (CAUSAL) tc.t = T128 - 1 - tc.t;  // key tile 0 is the heaviest: first
+  const int N = p.N;
+  const int G = p.Hq / p.Hkv;
+  const int g = tc.hq;
+  const int k0 = tc.t * BM;
+  const int wk0 = k0 + w * 32;  // first key of this wave
+  const int krow = wk0 + ki;
+
+  const size_t koff = ((size_t)(tc.b * p.Hkv + g) * N) * ROWB;
+  const int nqt_all = (N + BN - 1) / BN;
+  const int qt0 = CAUSAL ? k0 / BN : 0;
+  const int nt = G * (nqt_all - qt0);
+
+  int ld_row[NLD];
+  uint32_t ld_off[NLD];
+#pragma unroll
+  for (int it = 0; it < NLD; ++it) {
+    const int s = it * NT + tid;
+    const int r = s / NCH, c = s % NCH;
+    ld_row[it] = r;
+    ld_off[it] = r * ROWB + ((c ^ swz_rt(r)) << 4);
+  }
+  const uint32_t lds_base = (uint32_t)(uintptr_t)smem;
+  const uint32_t lds_wave = lds_base + w * 1024;
+  int iss_h = g * G, iss_qt = qt0;  // the next tile to request: query head and query tile
+  auto issue_next = [&](int slot) __attribute__((always_inline)) {
+    const size_t hoff = ((size_t)(tc.b * p.Hq + iss_h) * N) * ROWB + (size_t)iss_qt * TILEB;
+    const char* const qb = (const char*)p.q + hoff;
+    const char* const db = (const char*)p.dout + hoff;
+#pragma unroll
+    for (int it = 0; it < NLD; ++it) {
+      const uint32_t over = (uint32_t)max(0, iss_qt * BN + ld_row[it] - (N - 1)) * ROWB;  // rows past N-1 re-read row N-1
+      attn_lds_dma16(qb, ld_off[it] - over, lds_wave + slot * TILEB + it * NT * 16);
+      attn_lds_dma16(db, ld_off[it] - over, lds_wave + C::T2BASE + slot * TILEB + it * NT * 16);
+    }
+    const float* const wsrow = p.ws + (size_t)(tc.b * p.Hq + iss_h) * 2 * p.Npad + (size_t)iss_qt * BN;
+    const uint32_t aoff = (uint32_t)(((lane & 15) * 4 + ((lane >> 4) & 1) * p.Npad) * 4);
+    if (lane < 32) attn_lds_dma16(wsrow, aoff, lds_base + C::AUXBASE + slot * 512);
+    if (++iss_qt == nqt_all) {
+      iss_qt = qt0;
+      ++iss_h;
+    }
+  };
+  constexpr int LPT = 2 * NLD + 1;  // loads per thread and tile
+  issue_next(0);
+
+  bf16x8 kf[NKK], vf[NKK];
+  {
+    const int row = min(krow, N - 1);
+    const char* ks = (const char*)p.k + koff + (size_t)row * ROWB + h * 16;
+    const char* vs = (const char*)p.v + koff + (size_t)row * ROWB + h * 16;
+#pragma unroll
+    for (int kk = 0; kk < NKK; ++kk) {
+      kf[kk] = *(const bf16x8*)(ks + kk * 32);
+      vf[kk] = *(const bf16x8*)(vs + kk * 32);
+    }
+  }
+  if (nt > 1) issue_next(1);
+  if (nt > 2) issue_next(2);
+
+  uint32_t raddr[NKK];
+#pragma unroll
+  for (int kk = 0; kk < NKK; ++kk) raddr[kk] = ki * ROWB + (((2 * kk + h) ^ swz_rt(ki)) << 4);
+  uint32_t taddr[NCB][2];
+  {
+    const int s = lane & 15, chalf = (lane >> 4) & 1;
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+      for (int e = 0; e < 2; ++e) {
+        const int row = 8 * e + 4 * h + (s >> 2);
+        const int chunk = cb * 4 + chalf * 2 + ((s & 3) >> 1);
+        taddr[cb][e] = row * ROWB + ((chunk ^ swz_rt(row)) << 4) + ((s & 1) << 3);
+      }
+  }
+  auto row_operand = [&](int base, int kk) __attribute__((always_inline)) { return *(LDS_AS u32x4*)(smem + raddr[kk] + base); };
+  auto tr_operand = [&](int base, int cb, int kc) __attribute__((always_inline)) {
+    const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(smem + taddr[cb][0] + base + kc * 16 * ROWB));
+    const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(smem + taddr[cb][1] + base + kc * 16 * ROWB));
+    s16x8 av;
+    av[0] = v0[0]; av[1] = v0[1]; av[2] = v0[2]; av[3] = v0[3];
+    av[4] = v1[0]; av[5] = v1[1]; av[6] = v1[2]; av[7] = v1[3];
+    return __builtin_bit_cast(u32x4, av);
+  };
+  // operand of gradient product i of the block at `base`: dV^T += dO^T P (even i), dK^T += Q^T dS (odd i)
+  auto grad_operand = [&](int base, int i) __attribute__((always_inline)) {
+    return tr_operand(base + ((i & 1) ? 0 : C::T2BASE), (i >> 1) & 3, i >> 3);
+  };
+  // operand of score product i of the block at `base`: S += Q K^T (even i), dP += dO V^T (odd i)
+  auto score_operand = [&](int base, int i) __attribute__((always_inline)) {
+    return row_operand(base + ((i & 1) ? C::T2BASE : 0), i >> 1);
+  };
+
+  f32x16 acc_dv[NCB], acc_dk[NCB];
+#pragma unroll
+  for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc_dv[cb][r] = acc_dk[cb][r] = 0.f;
+  const float c = p.scale_log2;
+
+  u32x4 pre[RA];  // operands of the next step's first RA MFMAs
+  // One step.  (s_in, dp_in): finished scores of the block at base_cur whose first query row is q0b;
+  // (s_out, dp_out) <- scores of the block at base_next; (pp_out, pd_out) <- P and dS of the block
+  // at base_cur; (pp_acc, pd_acc): P and dS of the block at base_prev, multiplied into dV and dK.
+  auto step = [&](f32x16& s_in, f32x16& dp_in, f32x16& s_out, f32x16& dp_out, u32x4 (&pp_out)[2], u32x4 (&pd_out)[2],
+                  const u32x4 (&pp_acc)[2], const u32x4 (&pd_acc)[2], int base_prev, int base_cur, int base_next, int aux_off,
+                  int q0b) __attribute__((always_inline)) {
+    if (CAUSAL && q0b < wk0 + 31) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        if (q0b + 8 * (r >> 2) + 4 * h + (r & 3) < krow) s_in[r] = -INFINITY;
+    }
+    const LDS_AS float* const aux = (const LDS_AS float*)(smem + C::AUXBASE + aux_off) + 4 * h;
+    u32x4 op[NM];
+#pragma unroll
+    for (int m = 0; m < RA; ++m) op[m] = pre[m];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s_out[r] = dp_out[r] = 0.f;
+    f32x4 l4[4], d4[4];
+    float e_even = 0.f, f_even = 0.f;
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int m = 0; m < NM; ++m) {
+      // LDS reads: the operand of slot m + RA, and the statistics of the rows handled six slots on
+      if (m + RA < NM) op[m + RA] = C::is_score(m + RA) ? score_operand(base_next, C::index(m + RA)) : grad_operand(base_prev, C::index(m + RA));
+      else pre[m + RA - NM] = grad_operand(base_cur, m + RA - NM);
+#pragma unroll
+      for (int a = 0; a < 4; ++a)
+        if (C::aslot(a) == m) {
+          l4[a] = *(const LDS_AS f32x4*)(aux + 8 * a);
+          d4[a] = *(const LDS_AS f32x4*)(aux + 64 + 8 * a);
+        }
+      // the matrix product of this slot
+      const int i = C::index(m);
+      if (C::is_score(m)) {
+        if (i & 1) dp_out = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, op[m]), vf[i >> 1], dp_out, 0, 0, 0);
+        else s_out = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, op[m]), kf[i >> 1], s_out, 0, 0, 0);
+      } else {
+        const int cb = (i >> 1) & 3, kc = i >> 3;
+        if (i & 1) acc_dk[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, op[m]), __builtin_bit_cast(bf16x8, pd_acc[kc]), acc_dk[cb], 0, 0, 0);
+        else acc_dv[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, op[m]), __builtin_bit_cast(bf16x8, pp_acc[kc]), acc_dv[cb], 0, 0, 0);
+      }
+      // vector work: P = exp2(s c - lse2), dS = P (dP - delta) for the rows of this slot
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        if (C::vslot(r) == m) {
+          const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(s_in[r], c, -l4[r >> 2][r & 3]));
+          const float f = e * (dp_in[r] - d4[r >> 2][r & 3]);
+          if (r & 1) {
+            pp_out[r >> 3][(r >> 1) & 3] = pack_bf16(e_even, e);
+            pd_out[r >> 3][(r >> 1) & 3] = pack_bf16(f_even, f);
+          } else {
+            e_even = e;
+            f_even = f;
+          }
+        }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+#ifdef ATTN_BWD_PIN
+    // the finished scores are read by vector instructions next: keep them in vector registers
+#pragma unroll
+    for (int r = 0; r < 16; ++r) asm volatile("" : "+v"(s_out[r]), "+v"(dp_out[r]));
+#endif
+  };
+
+  if (nt > 2) ATTN_WAIT_VMCNT(2 * LPT);
+  else if (nt > 1) ATTN_WAIT_VMCNT(LPT);
+  else ATTN_WAIT_VMCNT(0);
+#pragma unroll
+  for (int kk = 0; kk < NKK; ++kk) asm volatile("" ::"v"(kf[kk]), "v"(vf[kk]));
+  attn_wg_barrier();
+
+  // prologue: scores of block 0; there is no block -1, its P and dS are zero and its operands are
+  // read from block 0 (finite data)
+  f32x16 sa, dpa, sb, dpb;
+  u32x4 ppa[2], pda[2], ppb[2], pdb[2];
+#pragma unroll
+  for (int r = 0; r < 16; ++r) sa[r] = dpa[r] = 0.f;
+#pragma unroll
+  for (int kk = 0; kk < NKK; ++kk) {
+    sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, row_operand(0, kk)), kf[kk], sa, 0, 0, 0);
+    dpa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, row_operand(C::T2BASE, kk)), vf[kk], dpa, 0, 0, 0);
+  }
+#pragma unroll
+  for (int t = 0; t < 2; ++t) ppb[t] = pdb[t] = u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+  for (int m = 0; m < RA; ++m) pre[m] = grad_operand(0, m);
+
+  int qt = qt0;
+  int bprev = 0;
+  for (int j = 0; j < nt; ++j) {
+    const int slot = j & (NSLOT - 1), nslot = (j + 1) & (NSLOT - 1);
+    const int b0 = slot * TILEB, b1 = b0 + SUBB;
+    const int q0b = qt * BN;
+    step(sa, dpa, sb, dpb, ppa, pda, ppb, pdb, bprev, b0, b1, slot * 512, q0b);
+    // tile j+1 has landed (the loads of tile j+2 stay in flight); every wave is done with tile j-1
+    if (j + 2 < nt) ATTN_WAIT_VMCNT(LPT);
+    else ATTN_WAIT_VMCNT(0);
+    attn_wg_barrier();
+    if (j + 3 < nt) issue_next((j + 3) & (NSLOT - 1));
+    step(sb, dpb, sa, dpa, ppb, pdb, ppa, pda, b0, b1, nslot * TILEB, slot * 512 + 128, q0b + 32);
+    bprev = b1;
+    if (++qt == nqt_all) qt = qt0;
+  }
+  // epilogue: the gradient products of the last block
+#pragma unroll
+  for (int i = RA; i < 16; ++i) {
+    const u32x4 o = grad_operand(bprev, i);
+    const int cb = (i >> 1) & 3, kc = i >> 3;
+    if (i & 1) acc_dk[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, o), __builtin_bit_cast(bf16x8, pdb[kc]), acc_dk[cb], 0, 0, 0);
+    else acc_dv[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, o), __builtin_bit_cast(bf16x8, ppb[kc]), acc_dv[cb], 0, 0, 0);
+  }
+#pragma unroll
+  for (int i = 0; i < RA; ++i) {
+    const int cb = (i >> 1) & 3, kc = i >> 3;
+    if (i & 1) acc_dk[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, pre[i]), __builtin_bit_cast(bf16x8, pdb[kc]), acc_dk[cb], 0, 0, 0);
+    else acc_dv[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, pre[i]), __builtin_bit_cast(bf16x8, ppb[kc]), acc_dv[cb], 0, 0, 0);
+  }
+
+  const size_t roff = koff + (size_t)min(krow, N - 1) * ROWB;
+  store_transposed<NCB>(acc_dv, 1.0f, (char*)p.dv + roff, h, krow < N);
+  store_transposed<NCB>(acc_dk, p.scale, (char*)p.dk + roff, h, krow < N);
+}
+
 }  // namespace
 
 int attn_bwd_launch_bf16_d128(const AttnBwdParams& p, hipStream_t stream) {
@@ -473,10 +755,18 @@ int attn_bwd_launch_bf16_d128(const AttnBwdParams& p, hipStream_t stream) {
   const int grid_f = p.B * p.Hkv * ((p.N + 127) / 128);
   if (p.causal) {
     hipLaunchKernelGGL((attn_bwd_dq_kernel<true>), dim3(grid_q), dim3(512), 0, stream, p);
+#ifdef ATTN_BWD_OLD
     hipLaunchKernelGGL((attn_bwd_dkv_fused_kernel<true>), dim3(grid_f), dim3(256), 0, stream, p);
+#else
+    hipLaunchKernelGGL((attn_bwd_dkv_pipe_kernel<true>), dim3(grid_f), dim3(256), 0, stream, p);
+#endif
   } else {
     hipLaunchKernelGGL((attn_bwd_dq_kernel<false>), dim3(grid_q), dim3(512), 0, stream, p);
+#ifdef ATTN_BWD_OLD
     hipLaunchKernelGGL((attn_bwd_dkv_fused_kernel<false>), dim3(grid_f), dim3(256), 0, stream, p);
+#else
+    hipLaunchKernelGGL((attn_bwd_dkv_pipe_kernel<false>), dim3(grid_f), dim3(256), 0, stream, p);
+#endif
   }
   return (int)hipGetLastError();
 }
