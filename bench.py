@@ -257,6 +257,32 @@ def time_gemm(A, torch, shapes, variants=(None,)):
                          "ms": ms, "TFLOP/s": tf, "pct_of_dense_peak": 100 * tf / PEAK_TFLOPS["bf16"]})
             log(f"[bench] gemm {g['name']} [{rows[-1]['variant']}]: {ms:.4f} ms  {tf:.1f} TFLOP/s = "
                 f"{100 * tf / PEAK_TFLOPS['bf16']:.1f}%")
+        # split-K with the slice count the library recommends (and a sweep of counts with --gemm-variants)
+        plan = A.gemm_splitk_plan(M, N, K)
+        counts = [plan] if plan > 1 else []
+        if len(variants) > 1 and K % 64 == 0 and K >= 4096:
+            counts = sorted(set(counts) | {2, 4, 8, 16})
+        for splits in counts:
+            ws = torch.empty(A.gemm_splitk_workspace_bytes(M, N, splits) // 4, dtype=torch.float32, device="cuda")
+
+            def step_sk():
+                A.gemm_bf16_nt_splitk(a, b, c, M, N, K, splits, ws, stream=stream)
+
+            for _ in range(max(3, min(200, int(0.05 / est)))):
+                step_sk()
+            torch.cuda.synchronize()
+            evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+            for e0, e1 in evs:
+                e0.record(stream)
+                step_sk()
+                e1.record(stream)
+            torch.cuda.synchronize()
+            ms = float(np.median([e0.elapsed_time(e1) for e0, e1 in evs]))
+            tf = flops / (ms * 1e-3) / 1e12
+            tag = f"split-K, {splits} slices" + (" (recommended)" if splits == plan else "")
+            rows.append({"workload": g["name"], "variant": tag, "ms": ms, "TFLOP/s": tf, "pct_of_dense_peak": 100 * tf / PEAK_TFLOPS["bf16"]})
+            log(f"[bench] gemm {g['name']} [{tag}]: {ms:.4f} ms  {tf:.1f} TFLOP/s = {100 * tf / PEAK_TFLOPS['bf16']:.1f}%")
+            del ws
         if g["name"] in ("mi350_2048", "canonical_k4096", "canonical_k8192") and N % 8 == 0:
             bkn = b.t().contiguous()  # the second operand stored [K, N]
 

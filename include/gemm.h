@@ -45,6 +45,26 @@ int gemm_bf16_nt(const void* a, const void* b, void* c, int M, int N, int K, voi
  */
 int gemm_bf16_nn(const void* a, const void* b, void* c, int M, int N, int K, void* stream);
 
+/*
+ * gemm_bf16_nt_splitk -- gemm_bf16_nt for outputs with too few 256 x 256 tiles to occupy the
+ * chip while K is long (the large-K rows of the paper's appendix A GEMM shape table): every
+ * output tile is computed by `splits` workgroups, each contracting one slice of k in fp32, and a
+ * second kernel adds the slices in index order and rounds to bfloat16.  Deterministic.
+ *   splits     1 .. 64 slices per tile; slices are whole multiples of 64 in k, so fewer may be
+ *              used than asked for (a slice is never empty)
+ *   workspace  device, gemm_splitk_workspace_bytes(M, N, splits) bytes, 16-byte aligned, owned by
+ *              the caller; contents on entry are irrelevant, contents on return unspecified
+ *   K          positive multiple of 64 (ATTN_ERR_UNSUPPORTED otherwise)
+ * Everything else, and the error behaviour, as for gemm_bf16_nt.  Two kernels are enqueued.
+ */
+int gemm_bf16_nt_splitk(const void* a, const void* b, void* c, int M, int N, int K, int splits,
+                        float* workspace, void* stream);
+/* bytes of fp32 workspace for that call: splits * M * N * 4 (0 for non-positive arguments) */
+long long gemm_splitk_workspace_bytes(int M, int N, int splits);
+/* The number of slices the library recommends for a shape: 1 means gemm_bf16_nt is the better
+ * call (enough tiles, or too little k per slice), more means gemm_bf16_nt_splitk with that many. */
+int gemm_splitk_plan(int M, int N, int K);
+
 /* Tuning hook: the same with kernel variant `variant` (0 .. gemm_num_variants()-1);
  * ATTN_ERR_UNSUPPORTED if K is not a multiple of that variant's K-slice. */
 int gemm_bf16_nt_variant(const void* a, const void* b, void* c, int M, int N, int K, int variant, void* stream);

@@ -46,6 +46,12 @@ lib.gemm_bf16_nt.argtypes = [_vp, _vp, _vp, _i, _i, _i, _vp]
 lib.gemm_bf16_nt.restype = _i
 lib.gemm_bf16_nn.argtypes = [_vp, _vp, _vp, _i, _i, _i, _vp]
 lib.gemm_bf16_nn.restype = _i
+lib.gemm_bf16_nt_splitk.argtypes = [_vp, _vp, _vp, _i, _i, _i, _i, _vp, _vp]
+lib.gemm_bf16_nt_splitk.restype = _i
+lib.gemm_splitk_workspace_bytes.argtypes = [_i, _i, _i]
+lib.gemm_splitk_workspace_bytes.restype = C.c_longlong
+lib.gemm_splitk_plan.argtypes = [_i, _i, _i]
+lib.gemm_splitk_plan.restype = _i
 lib.gemm_bf16_nt_variant.argtypes = [_vp, _vp, _vp, _i, _i, _i, _i, _vp]
 lib.gemm_bf16_nt_variant.restype = _i
 lib.gemm_num_variants.argtypes = []
@@ -232,3 +238,18 @@ def gemm_bf16_nn(a, b, c, M, N, K, stream=None, check=True):
     if check and st != 0:
         raise AttnError(st, "gemm_bf16_nn")
     return st
+
+
+def gemm_bf16_nt_splitk(a, b, c, M, N, K, splits, workspace, stream=None, check=True):
+    st = lib.gemm_bf16_nt_splitk(_ptr(a), _ptr(b), _ptr(c), M, N, K, int(splits), _ptr(workspace), _stream(stream))
+    if check and st != 0:
+        raise AttnError(st, "gemm_bf16_nt_splitk")
+    return st
+
+
+def gemm_splitk_workspace_bytes(M: int, N: int, splits: int) -> int:
+    return lib.gemm_splitk_workspace_bytes(M, N, splits)
+
+
+def gemm_splitk_plan(M: int, N: int, K: int) -> int:
+    return lib.gemm_splitk_plan(M, N, K)

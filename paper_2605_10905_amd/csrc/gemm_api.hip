@@ -71,9 +71,51 @@ int run_nn(const void* a, const void* b, void* c, int M, int N, int K, void* str
   return v.launch(p, (hipStream_t)stream) == 0 ? ATTN_OK : ATTN_ERR_LAUNCH;
 }
 
+int run_splitk(const void* a, const void* b, void* c, int M, int N, int K, int splits, float* workspace, void* stream) {
+  if (!a || !b || !c || !workspace) return ATTN_ERR_NULL;
+  if (M <= 0 || N <= 0 || K <= 0 || splits < 1 || splits > 64) return ATTN_ERR_SHAPE;
+  if (misaligned(a, 16) || misaligned(b, 16) || misaligned(c, 16) || misaligned(workspace, 16)) return ATTN_ERR_SHAPE;
+  if (K % 64 != 0) return ATTN_ERR_UNSUPPORTED;
+  if ((long long)K * 2 * 256 >= (1ll << 31)) return ATTN_ERR_UNSUPPORTED;
+  GemmParams p;
+  p.a = a; p.b = b; p.c = c;
+  p.M = M; p.N = N; p.K = K;
+  p.tiles_m = (M + 255) / 256;
+  p.tiles_n = (N + 255) / 256;
+  // slices of whole 64-column steps, none empty
+  const int steps = K / 64;
+  p.klen = ((steps + splits - 1) / splits) * 64;
+  p.splits = (K + p.klen - 1) / p.klen;
+  p.partial = workspace;
+  if ((long long)p.tiles_m * p.tiles_n * p.splits > 0x7fffffffll) return ATTN_ERR_UNSUPPORTED;
+  return gemm_bf16_nt_splitk_launch(p, (hipStream_t)stream) == 0 ? ATTN_OK : ATTN_ERR_LAUNCH;
+}
+
 }  // namespace
 
 extern "C" {
+
+int gemm_bf16_nt_splitk(const void* a, const void* b, void* c, int M, int N, int K, int splits, float* workspace, void* stream) {
+  return run_splitk(a, b, c, M, N, K, splits, workspace, stream);
+}
+
+long long gemm_splitk_workspace_bytes(int M, int N, int splits) {
+  if (M <= 0 || N <= 0 || splits <= 0) return 0;
+  return (long long)splits * M * N * 4;
+}
+
+// Measured on the paper's large-K shapes: splitting pays when the 256 x 256 tiles leave at least half
+// of the 256 CUs idle and every slice still has 2048 or more of k to amortise its prologue and the
+// fp32 round trip of the partial tiles.
+int gemm_splitk_plan(int M, int N, int K) {
+  if (M <= 0 || N <= 0 || K <= 0 || K % 64 != 0) return 1;
+  const long long tiles = (long long)((M + 255) / 256) * ((N + 255) / 256);
+  if (tiles > 128) return 1;
+  long long s = 256 / tiles;
+  if (s > K / 2048) s = K / 2048;
+  if (s > 64) s = 64;
+  return s < 2 ? 1 : (int)s;
+}
 
 int gemm_bf16_nn(const void* a, const void* b, void* c, int M, int N, int K, void* stream) {
   return run_nn(a, b, c, M, N, K, stream);

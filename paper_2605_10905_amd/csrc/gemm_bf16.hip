@@ -280,7 +280,9 @@ __global__ void __launch_bounds__(256, MINW) gemm_bf16_kernel(const GemmParams p
 // lane, lane (j, g) = row j, k 8g .. 8g+7) feeds eight MFMAs.  Same ring, same barrier placement.
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
-template <int BK, int NSTAGE>
+// SPLITK: the grid holds p.splits workgroups per tile; workgroup (split, tile) contracts its slice
+// of k and stores the fp32 accumulators to p.partial instead of rounding them into c.
+template <int BK, int NSTAGE, bool SPLITK>
 __global__ void __launch_bounds__(256, 1) gemm_bf16_nt_m16_kernel(const GemmParams p) {
   using C = GemmCfg<4, 4, BK, NSTAGE>;
   constexpr int ROWB = C::ROWB, NCH = C::NCH, TILEA = C::TILEA, STAGEB = C::STAGEB;
@@ -297,10 +299,14 @@ __global__ void __launch_bounds__(256, 1) gemm_bf16_nt_m16_kernel(const GemmPara
   const int lj = lane & 15, g = lane >> 4;
   const int wm = w >> 1, wn = w & 1;
 
-  const GemmTileCoord tc = gemm_tile_coord_impl(blockIdx.x, p.tiles_m, p.tiles_n);
+  const int ntile = p.tiles_m * p.tiles_n;
+  const int split = SPLITK ? (int)blockIdx.x / ntile : 0;
+  const GemmTileCoord tc = gemm_tile_coord_impl(SPLITK ? (int)blockIdx.x - split * ntile : (int)blockIdx.x, p.tiles_m, p.tiles_n);
   const int m0 = tc.tm * C::BM, n0 = tc.tn * C::BN;
   const int M = p.M, N = p.N, K = p.K;
   const size_t rowbytes = (size_t)K * 2;
+  const int kbeg = SPLITK ? split * p.klen : 0;            // this workgroup's slice of k
+  const int kcnt = SPLITK ? min(p.klen, K - kbeg) : K;
 
   uint32_t g_off[LPS];
 #pragma unroll
@@ -311,15 +317,15 @@ __global__ void __launch_bounds__(256, 1) gemm_bf16_nt_m16_kernel(const GemmPara
     const int row = is_a ? min(m0 + r, M - 1) - m0 : min(n0 + r, N - 1) - n0;
     g_off[it] = (uint32_t)row * (uint32_t)rowbytes + c * 16;
   }
-  const char* const a_tile = (const char*)p.a + (size_t)m0 * rowbytes;
-  const char* const b_tile = (const char*)p.b + (size_t)n0 * rowbytes;
+  const char* const a_tile = (const char*)p.a + (size_t)m0 * rowbytes + (size_t)kbeg * 2;
+  const char* const b_tile = (const char*)p.b + (size_t)n0 * rowbytes + (size_t)kbeg * 2;
   const uint32_t lds_wave = (uint32_t)(uintptr_t)smem + w * 1024;
   auto issue_load = [&](int ks, int slot, int it) __attribute__((always_inline)) {
     if (it < NLDA) attn_lds_dma16(a_tile + (size_t)ks * ROWB, g_off[it], lds_wave + slot * STAGEB + it * C::NT * 16);
     else attn_lds_dma16(b_tile + (size_t)ks * ROWB, g_off[it], lds_wave + slot * STAGEB + TILEA + (it - NLDA) * C::NT * 16);
   };
 
-  const int nk = K / BK;
+  const int nk = kcnt / BK;
 #pragma unroll
   for (int s = 0; s < NSTAGE; ++s)
     if (s < nk) {
@@ -426,6 +432,29 @@ __global__ void __launch_bounds__(256, 1) gemm_bf16_nt_m16_kernel(const GemmPara
   // ---- epilogue: lane (lj, g) holds, for row m, the columns n = 16 nb + 4 g + (0..3); a pair of
   // neighbouring n blocks is exchanged between odd and even lane groups so that every lane owns 8
   // consecutive columns: one 16-byte store each
+  if (SPLITK) {
+    // fp32 partial tile: every lane owns 4 consecutive columns of row m, one 16-byte store
+    const bool vec4 = (N & 3) == 0;
+#pragma unroll
+    for (int mb = 0; mb < 8; ++mb) {
+      const int m = m0 + wm * 128 + mb * 16 + lj;
+      float* const prow = p.partial + ((size_t)split * M + (size_t)min(m, M - 1)) * N;
+#pragma unroll
+      for (int nb = 0; nb < 8; ++nb) {
+        const int n = n0 + wn * 128 + nb * 16 + 4 * g;
+        if (m < M) {
+          if (vec4 && n + 4 <= N) {
+            *(f32x4*)(prow + n) = acc[nb][mb];
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (n + e < N) prow[n + e] = acc[nb][mb][e];
+          }
+        }
+      }
+    }
+    return;
+  }
   const bool vec_ok = (N & 7) == 0;
 #pragma unroll
   for (int mb = 0; mb < 8; ++mb) {
@@ -461,8 +490,29 @@ __global__ void __launch_bounds__(256, 1) gemm_bf16_nt_m16_kernel(const GemmPara
 
 template <int BK, int NSTAGE>
 int launch_m16(const GemmParams& p, hipStream_t stream) {
-  hipLaunchKernelGGL((gemm_bf16_nt_m16_kernel<BK, NSTAGE>), dim3(p.tiles_m * p.tiles_n), dim3(256), 0, stream, p);
+  hipLaunchKernelGGL((gemm_bf16_nt_m16_kernel<BK, NSTAGE, false>), dim3(p.tiles_m * p.tiles_n), dim3(256), 0, stream, p);
   return (int)hipGetLastError();
+}
+
+// c[i] = bf16(sum over splits of partial[s][i]), splits added in index order; 8 elements per thread
+__global__ void __launch_bounds__(256) gemm_splitk_sum_kernel(const float* __restrict__ partial, void* c, size_t total, int splits) {
+  const size_t i8 = ((size_t)blockIdx.x * 256 + threadIdx.x) * 8;
+  if (i8 >= total) return;
+  if ((total & 7) == 0) {
+    f32x4 lo = *(const f32x4*)(partial + i8), hi = *(const f32x4*)(partial + i8 + 4);
+    for (int s = 1; s < splits; ++s) {
+      lo += *(const f32x4*)(partial + (size_t)s * total + i8);
+      hi += *(const f32x4*)(partial + (size_t)s * total + i8 + 4);
+    }
+    u32x4 out = {pack_bf16(lo[0], lo[1]), pack_bf16(lo[2], lo[3]), pack_bf16(hi[0], hi[1]), pack_bf16(hi[2], hi[3])};
+    *(u32x4*)((__bf16*)c + i8) = out;
+  } else {
+    for (size_t i = i8; i < i8 + 8 && i < total; ++i) {
+      float v = partial[i];
+      for (int s = 1; s < splits; ++s) v += partial[(size_t)s * total + i];
+      ((__bf16*)c)[i] = (__bf16)v;
+    }
+  }
 }
 
 template <int WM, int WN, int BK, int NSTAGE, int MINW, bool BKN = false>
@@ -472,6 +522,13 @@ int launch(const GemmParams& p, hipStream_t stream) {
 }
 
 }  // namespace
+
+int gemm_bf16_nt_splitk_launch(const GemmParams& p, hipStream_t stream) {
+  hipLaunchKernelGGL((gemm_bf16_nt_m16_kernel<32, 4, true>), dim3(p.tiles_m * p.tiles_n * p.splits), dim3(256), 0, stream, p);
+  const size_t total = (size_t)p.M * p.N;
+  hipLaunchKernelGGL(gemm_splitk_sum_kernel, dim3((unsigned)((total + 2047) / 2048)), dim3(256), 0, stream, p.partial, p.c, total, p.splits);
+  return (int)hipGetLastError();
+}
 
 const GemmVariant* gemm_bf16_nt_variants(int* count) {
   static const GemmVariant table[] = {

@@ -8,6 +8,11 @@ struct GemmParams {
   void* c;        // bf16 [M, N]
   int M, N, K;
   int tiles_m, tiles_n;
+  // split-K launches only: split s of `splits` contracts k in [s * klen, min(K, (s + 1) * klen)) and
+  // writes its fp32 partial tile to partial[s][M][N]; a second kernel sums the splits into c
+  float* partial = nullptr;
+  int splits = 1;
+  int klen = 0;
 };
 
 struct GemmVariant {
@@ -19,3 +24,5 @@ struct GemmVariant {
 
 const GemmVariant* gemm_bf16_nt_variants(int* count);
 const GemmVariant* gemm_bf16_nn_variants(int* count);  // second operand stored [K, N]
+// 256 x 256 tiles, K split over p.splits workgroups per tile (p.klen a multiple of 64), then the sum
+int gemm_bf16_nt_splitk_launch(const GemmParams& p, hipStream_t stream);

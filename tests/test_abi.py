@@ -141,3 +141,24 @@ def test_gemm_argument_validation_without_a_device(A):
     assert A.gemm_bf16_nt(p + 2, p, p, 64, 64, 64, stream=0, check=False) == 2
     assert A.gemm_bf16_nt_variant(p, p, p, 64, 64, 64, 10 ** 6, stream=0, check=False) == 4
     assert A.gemm_variant_tile(0) == 256 and A.gemm_variant_tile(-1) == 0
+
+
+def test_gemm_splitk_plan_and_validation_without_a_device(A):
+    p = 0x1000
+    assert A.gemm_bf16_nt_splitk(p, p, p, 64, 64, 96, 2, p, stream=0, check=False) == 4   # K % 64
+    assert A.gemm_bf16_nt_splitk(p, p, p, 64, 64, 64, 0, p, stream=0, check=False) == 2
+    assert A.gemm_bf16_nt_splitk(p, p, p, 64, 64, 64, 65, p, stream=0, check=False) == 2
+    assert A.gemm_bf16_nt_splitk(p, p, p, 64, 64, 64, 2, None, stream=0, check=False) == 1
+    assert A.gemm_bf16_nt_splitk(p, p, p, 64, 64, 64, 2, p + 4, stream=0, check=False) == 2
+    assert A.gemm_splitk_workspace_bytes(512, 4096, 8) == 8 * 512 * 4096 * 4
+    assert A.gemm_splitk_workspace_bytes(0, 4096, 8) == 0
+    # the paper's large-K shapes get slices that fill the 256 CUs, the others none
+    assert A.gemm_splitk_plan(512, 4096, 64512) == 8
+    assert A.gemm_splitk_plan(2304, 1024, 65536) == 7
+    assert A.gemm_splitk_plan(8192, 8192, 8192) == 1
+    assert A.gemm_splitk_plan(2048, 2048, 2048) == 1      # too little k per slice
+    assert A.gemm_splitk_plan(512, 512, 8200) == 1        # K not a multiple of 64
+    for M, N, K in [(512, 4096, 64512), (256, 256, 1 << 20), (1, 1, 4096), (2304, 1024, 65536)]:
+        s = A.gemm_splitk_plan(M, N, K)
+        tiles = -(-M // 256) * -(-N // 256)
+        assert 1 <= s <= 64 and (s == 1 or (tiles * s <= 256 and K // s >= 2048))

@@ -119,6 +119,76 @@ def test_gemm_full_size_sampled(name):
     print(check(c, a, b, f"gemm {name}", rows=rows), flush=True)
 
 
+# ---- split-K ------------------------------------------------------------------------------------------
+def run_gemm_splitk(a_bits, b_bits, splits, poison=float("nan")):
+    import paper_2605_10905_amd as A
+
+    M, K = a_bits.shape
+    N = b_bits.shape[0]
+    a, b = gu.bf16_to_device(a_bits), gu.bf16_to_device(b_bits)
+    c = torch.full((M, N), poison, dtype=torch.bfloat16, device="cuda")
+    ws = torch.full((A.gemm_splitk_workspace_bytes(M, N, splits) // 4,), poison, dtype=torch.float32, device="cuda")
+    A.gemm_bf16_nt_splitk(a, b, c, M, N, K, splits, ws)
+    torch.cuda.synchronize()
+    return c
+
+
+# one and several tiles, ragged M and N (vector and scalar stores of the partial tiles and of C),
+# slices that divide K evenly, a shorter last slice, more slices asked for than k-steps exist
+SPLITK = [(256, 256, 512, 2), (300, 520, 4032, 4), (513, 257, 1024, 8), (64, 7, 640, 3), (5, 3, 128, 64), (1000, 72, 2048, 1),
+          (512, 384, 8192, 16), (33, 1001, 4096, 5)]
+
+
+@pytest.mark.parametrize("M,N,K,splits", SPLITK)
+def test_gemm_splitk_shapes(M, N, K, splits):
+    a, b = wl.make_gemm_inputs(700 + M + N + K, M, N, K)
+    print(f"gemm split-K {M}x{N}x{K} splits {splits}", flush=True)
+    c = run_gemm_splitk(a, b, splits)
+    check(c, a, b, f"gemm split-K {M}x{N}x{K} / {splits}")
+    c2 = run_gemm_splitk(a, b, splits, poison=1.0e30)  # deterministic, and no stale workspace value is read
+    assert torch.equal(c.view(torch.int16), c2.view(torch.int16))
+
+
+def test_gemm_splitk_structured_and_unsupported():
+    import paper_2605_10905_amd as A
+
+    M, N, K = 384, 320, 1024
+    rng = np.random.default_rng(5)
+    a = rng.standard_normal((M, K)).astype(np.float32)
+    b = np.zeros((N, K), dtype=np.float32)
+    cols = rng.integers(0, K, N)
+    b[np.arange(N), cols] = 1.0  # one-hot rows: C[m, n] = A[m, cols[n]] exactly, whichever slice holds the column
+    ab, bb = wl.f32_to_bf16_bits(a), wl.f32_to_bf16_bits(b)
+    c = run_gemm_splitk(ab, bb, 4)
+    want = torch.from_numpy(ab.view(np.int16)).view(torch.bfloat16)[:, torch.from_numpy(cols)]
+    assert torch.equal(c.cpu().view(torch.int16), want.contiguous().view(torch.int16))
+    t = torch.zeros(64 * 64, dtype=torch.bfloat16, device="cuda")
+    w = torch.zeros(64 * 64 * 4, dtype=torch.float32, device="cuda")
+    assert A.gemm_bf16_nt_splitk(t, t, t, 64, 64, 96, 2, w, check=False) != 0    # K not a multiple of 64
+    assert A.gemm_bf16_nt_splitk(t, t, t, 64, 64, 64, 0, w, check=False) != 0    # no slices
+    assert A.gemm_bf16_nt_splitk(t, t, t, 64, 64, 64, 65, w, check=False) != 0
+    assert A.gemm_bf16_nt_splitk(t, t, t, 64, 64, 64, 2, None, check=False) != 0
+
+
+@pytest.mark.parametrize("name", ["large_k_512x4096x64512", "large_k_2304x1024x65536"])
+def test_gemm_splitk_full_size_sampled(name):
+    """The paper's large-K shapes with the slice count the library recommends, as bench.py times them."""
+    import paper_2605_10905_amd as A
+
+    g = next(s for s in wl.GEMM_SHAPES if s["name"] == name)
+    M, N, K = g["M"], g["N"], g["K"]
+    splits = A.gemm_splitk_plan(M, N, K)
+    assert splits > 1
+    print(f"gemm split-K full size {name}: {splits} slices, generating inputs", flush=True)
+    a, b = wl.make_gemm_inputs(g["seed"], M, N, K)
+    c = run_gemm_splitk(a, b, splits)
+    assert bool(torch.isfinite(c.float()).all())
+    rng = np.random.default_rng(g["seed"])
+    rows = sorted({0, 1, 255, 256, M - 1, M // 2, *(int(r) for r in rng.integers(0, M, 16))} & set(range(M)))
+    print(f"gemm split-K full size {name}: oracle on {len(rows)} rows", flush=True)
+    print(check(c, a, b, f"gemm split-K {name}", rows=rows), flush=True)
+
+
 # ---- second operand stored [K, N] ---------------------------------------------------------------------
 def run_gemm_nn(a_bits, bkn_bits, poison=float("nan")):
     import paper_2605_10905_amd as A
