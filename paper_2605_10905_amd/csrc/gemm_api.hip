@@ -24,7 +24,9 @@ int choose(int M, int N, int K, const GemmVariant* table, int count) {
   auto tiles = [&](int t) { return (long long)((M + t - 1) / t) * ((N + t - 1) / t); };
   int v = -1;
   // (256 tile: the 16x16x32 MFMA form is 2-4 % faster at the same power; it runs its stages in pairs)
-  if (tiles(256) >= 200) v = find(table, count, 256, 32, K % 64 == 0 ? 1 : 0);
+  // (with at most four of its k-stages the ring of two 64-column stages starts and drains faster
+  // than the ring of four 32-column ones: 8-12 % on the K <= 256 shapes of the paper's tables)
+  if (tiles(256) >= 200) v = K % 64 == 0 && K <= 256 ? find(table, count, 256, 64, 1) : find(table, count, 256, 32, K % 64 == 0 ? 1 : 0);
   else if (tiles(128) >= 100 && K % 64 == 0) v = find(table, count, 128, 64, 1);
   if (v < 0) v = find(table, count, 64, 32, 0);
   return v;
