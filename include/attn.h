@@ -1,7 +1,8 @@
 /*
- * attn.h -- C ABI of the MI355X (gfx950) fused attention forward library.
+ * attn.h -- C ABI of the MI355X (gfx950) fused attention library: the forward pass (attn_fwd and
+ * its variants), its persistent-launch form and the backward pass (attn_bwd).
  *
- * The operation is the fused scaled-dot-product attention forward pass of the
+ * The central operation is the fused scaled-dot-product attention forward pass of the
  * paper's section 6.1 ("Major Operators": tile staging, score computation,
  * masking, normalisation, output accumulation), with the two outputs its
  * appendix C.3 names: the normalised accumulator  O = acc / l  and the
