@@ -231,3 +231,52 @@ def test_gemm_nn_structured_and_unsupported():
     t = torch.zeros(64 * 64, dtype=torch.bfloat16, device="cuda")
     assert A.gemm_bf16_nn(t, t, t, 64, 60, 32, check=False) != 0   # N not a multiple of 8
     assert A.gemm_bf16_nn(t, t, t, 64, 64, 24, check=False) != 0   # K not a multiple of 32
+
+
+def test_gemm_calls_can_be_captured_in_a_graph_and_replayed():
+    """gemm_bf16_nt, gemm_bf16_nn and gemm_bf16_nt_splitk (two kernels) captured into one graph; every
+    replay, with eager work in between, must reproduce the eager results bit for bit."""
+    import paper_2605_10905_amd as A
+
+    M, N, K = 520, 392, 4096
+    ab, bb = wl.make_gemm_inputs(77, M, N, K)
+    a, b = gu.bf16_to_device(ab), gu.bf16_to_device(bb)
+    bkn = b.t().contiguous()
+    splits = 5
+
+    def buffers():
+        return dict(c=torch.zeros((M, N), dtype=torch.bfloat16, device="cuda"),
+                    cn=torch.zeros((M, N), dtype=torch.bfloat16, device="cuda"),
+                    cs=torch.zeros((M, N), dtype=torch.bfloat16, device="cuda"),
+                    ws=torch.zeros(A.gemm_splitk_workspace_bytes(M, N, splits) // 4, dtype=torch.float32, device="cuda"))
+
+    def run(t):
+        A.gemm_bf16_nt(a, b, t["c"], M, N, K)
+        A.gemm_bf16_nn(a, bkn, t["cn"], M, N, K)
+        A.gemm_bf16_nt_splitk(a, b, t["cs"], M, N, K, splits, t["ws"])
+
+    eager = buffers()
+    run(eager)
+    torch.cuda.synchronize()
+    check(eager["c"], ab, bb, "eager nt")
+    check(eager["cn"], ab, bb, "eager nn")
+    check(eager["cs"], ab, bb, "eager split-K")
+
+    cap = buffers()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run(cap)  # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        run(cap)
+    for rep in range(3):
+        for name in ("c", "cn", "cs", "ws"):
+            cap[name].fill_(7.0)  # eager work between the replays; also proves the replay rewrites everything
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for name in ("c", "cn", "cs"):
+            assert torch.equal(cap[name].view(torch.uint8), eager[name].view(torch.uint8)), f"replay {rep}: {name} differs"
