@@ -7,10 +7,13 @@ quoted on: B=2, Hq=Hkv=32, N=8192, d=128, bf16, non-causal, synthetic N(0,1)*0.5
 inputs already resident in HBM.  Prints ONE JSON line on stdout.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--config I] [--variant V]
-                  [--no-cpu-baseline] [--all-configs] [--paper-grid] [--copy-calibration]
+                  [--no-cpu-baseline] [--all-configs] [--paper-grid] [--copy-calibration] [--mfma-ceiling]
 
 --paper-grid also times the paper's own attention shape grid (appendix A: batch 4, 48 heads,
 N = 1024 .. 16384, d = 128, causal and non-causal) and reports it under 'paper_grid'.
+--mfma-ceiling also times the library's MFMA probe kernel: the rate the board sustains on the matrix
+pipe under its power limit, alone and with the forward kernel's LDS reads and vector work added:
+the practical ceiling beside the published peak.
 --copy-calibration runs nothing but a 1 GiB device-to-device copy (three times): under
 `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE` it gives the factor that converts those
 counters into bytes (see profiles/).
@@ -218,6 +221,37 @@ def time_backward(A, torch, cfgs):
     return rows
 
 
+def time_mfma_ceiling(A, torch):
+    """What the board sustains on the matrix pipe: the library's probe kernel (bf16 32x32x16 MFMAs in
+    the forward kernel's launch shape, no global memory traffic) run back to back for about 0.15 s per
+    pattern; the second half of the launches is averaged."""
+    sink = torch.empty(A.attn_mfma_probe_sink_floats(), dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream()
+    iters = 1000  # 1.2 - 1.7 ms per launch, the length of the headline kernel
+    flops = A.attn_mfma_probe_flops(iters)
+    rows = []
+    names = {1: "MFMA only, pseudo-random bf16 operands in registers",
+             2: "+ A operands read from LDS (1 KB per wave and MFMA)",
+             3: "+ LDS reads + one exponential / 2 fma / add / half a pack per MFMA and lane",
+             0: "MFMA only, zero operands"}
+    for pattern in (1, 2, 3, 0):
+        n = 100
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+        for e0, e1 in evs:
+            e0.record(stream)
+            A.attn_mfma_probe(iters, pattern, sink, stream=stream)
+            e1.record(stream)
+        torch.cuda.synchronize()
+        ms = [e0.elapsed_time(e1) for e0, e1 in evs]
+        late = float(np.mean(ms[n // 2:]))
+        tf = flops / (late * 1e-3) / 1e12
+        rows.append({"pattern": pattern, "what": names[pattern], "ms_per_launch": late, "first_launch_ms": ms[0], "TFLOP/s": tf,
+                     "pct_of_dense_peak": 100 * tf / PEAK_TFLOPS["bf16"], "flop_per_launch": flops})
+        log(f"[bench] probe {pattern} ({names[pattern]}): {late:.4f} ms per launch (first {ms[0]:.4f})  {tf:.1f} TFLOP/s = "
+            f"{100 * tf / PEAK_TFLOPS['bf16']:.1f}% of the published dense peak")
+    return rows
+
+
 def time_gemm(A, torch, shapes, variants=(None,)):
     """bf16 GEMM on the paper's shapes.  Inputs drawn on the device (seeded N(0,1) rounded to
     bf16); parity on these shapes is covered by the tests."""
@@ -370,6 +404,7 @@ def main():
     ap.add_argument("--gemm-shape", default=None, help="with --gemm: only this shape (a name in workloads.GEMM_SHAPES)")
     ap.add_argument("--gemm-variants", action="store_true", help="with --gemm: time every kernel variant")
     ap.add_argument("--copy-calibration", action="store_true", help="only run a 1 GiB copy (counter calibration)")
+    ap.add_argument("--mfma-ceiling", action="store_true", help="also time the MFMA-only probe kernel (what the board sustains on the matrix pipe alone)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (every (batch, head) is independent, so the path would "
@@ -457,6 +492,8 @@ def main():
         if args.paper_grid:
             cfgs += wl.paper_grid()
         out["persistent"] = time_persistent(A, torch, cfgs)
+    if args.mfma_ceiling:
+        out["mfma_ceiling"] = time_mfma_ceiling(A, torch)
     if args.gemm:
         variants = [None] + list(range(A.gemm_num_variants())) if args.gemm_variants else [None]
         shapes = [g for g in wl.GEMM_SHAPES if args.gemm_shape in (None, g["name"])]

@@ -149,6 +149,23 @@ int attn_num_workgroups(int B, int Hq, int N, int BM);
 /* Query-tile height BM (rows per workgroup) of a variant; 0 if out of range. */
 int attn_variant_bm(int variant);
 
+/*
+ * attn_mfma_probe -- measurement aid, not part of the attention path: enqueues a kernel in the
+ * launch shape of the attention forward (one workgroup of eight waves per CU) whose waves issue
+ * iters * 32 bf16 32x32x16 MFMAs each, with no global memory traffic, so that a benchmark can report
+ * what the board sustains on the matrix pipe under its power limit, alone and with the forward
+ * kernel's other ingredients added.
+ *   iters    0 .. 2^24
+ *   pattern  0: zero operands; 1: pseudo-random bf16 operands in registers; 2: the A operand of
+ *            every MFMA read from LDS (1 KB per wave and MFMA); 3: in addition one exponential and
+ *            the multiply-adds, add and bf16 pack that go with it per MFMA and lane
+ *   sink     device, attn_mfma_probe_sink_floats() floats, overwritten (keeps the work observable)
+ * attn_mfma_probe_flops(iters) is the number of MFMA flops the launch executes.
+ */
+int attn_mfma_probe(int iters, int pattern, float* sink, void* stream);
+int attn_mfma_probe_sink_floats(void);
+double attn_mfma_probe_flops(int iters);
+
 const char* attn_status_string(int status); /* host string, static storage */
 int attn_version(void);
 

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libattn_mi355x.so")
-SOURCES = ["attn_api.hip", "attn_fwd_bf16.hip", "attn_fwd_bf16_pp.hip", "attn_fwd_bf16_sp.hip", "attn_fwd_bf16_w16.hip", "attn_fwd_fp8.hip", "attn_fwd_fp8_sp.hip", "attn_fwd_fp8_cv.hip", "attn_fwd_fp8_hy.hip", "attn_bwd_bf16.hip", "gemm_api.hip", "gemm_bf16.hip"]
+SOURCES = ["attn_api.hip", "attn_fwd_bf16.hip", "attn_fwd_bf16_pp.hip", "attn_fwd_bf16_sp.hip", "attn_fwd_bf16_w16.hip", "attn_fwd_fp8.hip", "attn_fwd_fp8_sp.hip", "attn_fwd_fp8_cv.hip", "attn_fwd_fp8_hy.hip", "attn_bwd_bf16.hip", "gemm_api.hip", "gemm_bf16.hip", "mfma_probe.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed fp32 VALU forms are switched off on purpose (they have misbehaved on the test machines)
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

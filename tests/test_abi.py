@@ -162,3 +162,12 @@ def test_gemm_splitk_plan_and_validation_without_a_device(A):
         s = A.gemm_splitk_plan(M, N, K)
         tiles = -(-M // 256) * -(-N // 256)
         assert 1 <= s <= 64 and (s == 1 or (tiles * s <= 256 and K // s >= 2048))
+
+
+def test_mfma_probe_validation_without_a_device(A):
+    p = 0x1000
+    assert A.attn_mfma_probe(10, 1, None, stream=0, check=False) == 1
+    assert A.attn_mfma_probe(10, 4, p, stream=0, check=False) == 2
+    assert A.attn_mfma_probe(-1, 0, p, stream=0, check=False) == 2
+    assert A.attn_mfma_probe_sink_floats() == 256 * 512
+    assert A.attn_mfma_probe_flops(1000) == 1000 * 32 * 2 * 32 * 32 * 16 * 256 * 8
