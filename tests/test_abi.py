@@ -171,3 +171,20 @@ def test_mfma_probe_validation_without_a_device(A):
     assert A.attn_mfma_probe(-1, 0, p, stream=0, check=False) == 2
     assert A.attn_mfma_probe_sink_floats() == 256 * 512
     assert A.attn_mfma_probe_flops(1000) == 1000 * 32 * 2 * 32 * 32 * 16 * 256 * 8
+
+
+def test_mfma_lint_flags_early_use_of_an_inline_mfma_result():
+    """The build-time check behind the kernels that write MFMAs as inline assembly."""
+    from paper_2605_10905_amd import mfma_lint
+
+    head = "_Z1kv:\n"
+    mfma = "\t;;#ASMSTART\n\tv_mfma_f32_32x32x16_bf16 v[16:31], v[0:3], a[4:7], v[16:31]\n\t;;#ASMEND\n"
+    assert mfma_lint.lint(head + mfma + "\tv_add_f32_e32 v40, v41, v42\n" * 11 + "\tv_add_f32_e32 v40, v20, v42\n") == []
+    assert mfma_lint.lint(head + mfma + "\ts_nop 10\n\tv_accvgpr_write_b32 a9, v31\n") == []
+    assert mfma_lint.lint(head + mfma + mfma + mfma) == []                                   # in-place accumulation
+    bad = mfma_lint.lint(head + mfma + "\tv_add_f32_e32 v40, v41, v42\n" * 3 + "\tv_accvgpr_write_b32 a9, v31\n")
+    assert len(bad) == 1 and bad[0][2] == [31]
+    assert len(mfma_lint.lint(head + mfma + "\ts_nop 3\n\tv_exp_f32_e32 v16, v50\n")) == 1    # overwritten too early
+    assert len(mfma_lint.lint(head + mfma + "\tds_read_b128 v[28:31], v60\n")) == 1
+    # compiler-issued MFMAs are the compiler's business
+    assert mfma_lint.lint(head + "\tv_mfma_f32_32x32x16_bf16 v[16:31], v[0:3], v[4:7], v[16:31]\n\tv_mov_b32_e32 v1, v16\n") == []
