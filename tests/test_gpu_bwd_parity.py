@@ -141,3 +141,22 @@ def test_bwd_full_size(ci):
         print(f"bwd full-size config{ci + 1}: oracle on group b={b} g={g} ({G} query heads)", flush=True)
         m = gu.check_bwd_group(inp, dob, dq, dk, dv, b, g, f"bwd config{ci + 1} full size group {(b, g)}")
         print(f"bwd full-size config{ci + 1}: {m}", flush=True)
+
+
+def _random_bwd_shapes(seed, count, max_n):
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(count):
+        hkv = int(rng.integers(1, 4))
+        g = int(rng.choice([1, 2, 4]))
+        out.append((int(rng.integers(1, 3)), hkv * g, hkv, int(rng.integers(1, max_n + 1)), bool(rng.integers(0, 2)), int(rng.integers(1, 1 << 30))))
+    return out
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,N,causal,seed", _random_bwd_shapes(20260512, 16, 700))
+def test_bwd_random_shapes(B, Hq, Hkv, N, causal, seed):
+    """Seeded random batch / head / group / length / mask combinations."""
+    cfg, inp, dob = _case(1, B, Hq, Hkv, N, causal=causal, seed=seed)
+    print(f"bwd random B={B} Hq={Hq} Hkv={Hkv} N={N} causal={causal}", flush=True)
+    dq, dk, dv, _, _ = gu.run_gpu_bwd(inp, dob)
+    gu.check_bwd_full(inp, dob, dq, dk, dv, f"bwd random B={B} Hq={Hq} Hkv={Hkv} N={N} causal={causal}")

@@ -280,3 +280,22 @@ def test_gemm_calls_can_be_captured_in_a_graph_and_replayed():
         torch.cuda.synchronize()
         for name in ("c", "cn", "cs"):
             assert torch.equal(cap[name].view(torch.uint8), eager[name].view(torch.uint8)), f"replay {rep}: {name} differs"
+
+
+def _random_gemm_shapes(seed, count):
+    rng = np.random.default_rng(seed)
+    return [(int(rng.integers(1, 900)), int(rng.integers(1, 900)), 32 * int(rng.integers(1, 40))) for _ in range(count)]
+
+
+@pytest.mark.parametrize("M,N,K", _random_gemm_shapes(20260513, 12))
+def test_gemm_random_shapes(M, N, K):
+    """Seeded random shapes: the library's choice, the [K, N] layout where it applies, split-K where K allows."""
+    a, b = wl.make_gemm_inputs(900 + M + N + K, M, N, K)
+    print(f"gemm random {M}x{N}x{K}", flush=True)
+    check(run_gemm(a, b), a, b, f"gemm random {M}x{N}x{K}")
+    if N % 8 == 0:
+        bkn = np.ascontiguousarray(b.T)
+        c = run_gemm_nn(a, bkn)
+        check(c, a, b, f"gemm nn random {M}x{N}x{K}")
+    if K % 64 == 0:
+        check(run_gemm_splitk(a, b, 3), a, b, f"gemm split-K random {M}x{N}x{K}")

@@ -374,3 +374,26 @@ def test_mfma_probe_patterns_run():
             assert bool((sink == 0).all())
         else:
             assert bool((sink != 0).any())
+
+
+def _random_shapes(seed, count, max_n):
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(count):
+        hkv = int(rng.integers(1, 4))
+        g = int(rng.choice([1, 2, 4]))
+        out.append(dict(B=int(rng.integers(1, 3)), Hq=hkv * g, Hkv=hkv, N=int(rng.integers(1, max_n + 1)),
+                        d=int(rng.choice([64, 128])), causal=bool(rng.integers(0, 2)), seed=int(rng.integers(1, 1 << 30))))
+    return out
+
+
+@pytest.mark.parametrize("shape", _random_shapes(20260511, 24, 900), ids=lambda s: f"B{s['B']}H{s['Hq']}k{s['Hkv']}N{s['N']}d{s['d']}{'c' if s['causal'] else 'n'}")
+def test_random_shapes_every_variant(shape):
+    """Seeded random batch / head / group / length / mask combinations, every bf16 variant."""
+    cfg = dict(wl.CONFIGS[1], d=shape["d"], causal=shape["causal"], scale=1.0 / shape["d"] ** 0.5, seed=shape["seed"])
+    inp = wl.make_inputs(cfg, B=shape["B"], Hq=shape["Hq"], Hkv=shape["Hkv"], N=shape["N"])
+    dev = gu.to_device(inp)
+    for var in [None] + _variants(shape["d"]):
+        print(f"random shape {shape} variant {var}", flush=True)
+        o, lse = gu.run_gpu(inp, dev, var)
+        gu.check_full(inp, o, lse, f"random {shape} variant {var}")
