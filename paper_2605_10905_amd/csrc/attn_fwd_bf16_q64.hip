@@ -270,25 +270,24 @@ __global__ void __launch_bounds__(256, 1) attn_fwd_bf16_q64_kernel(const AttnPar
       for (int e = 0; e < 32; ++e)
         if (C::vslot(e) == m) {
           const int b2 = e >> 4, r = e & 15;
-          // (the add of an exponential waits one slot: the result of a transcendental instruction
-          // cannot be read by the instruction right behind it)
+          // (the add and the pack of an exponential wait one slot: the result of a transcendental
+          // instruction cannot be read by the instruction right behind it)
           if (e > 0) ls[(e - 1) >> 4] += e_last;
-          // the two empty statements keep this slot's vector work in this slot: the exponential
-          // cannot start before the first (its reference operand is defined there) and its pack
-          // cannot be delayed past the second
-          asm volatile("" : "+v"(mneg[b2]));
-          const float ev = __builtin_amdgcn_exp2f(__builtin_fmaf(s_in[b2][r], c, mneg[b2]));
-          e_last = ev;
-          if (r & 1) {
-            p_out[b2][r >> 3][(r >> 1) & 3] = pack_bf16(e_even, ev);
-            asm volatile("" ::"v"(p_out[b2][r >> 3][(r >> 1) & 3]));
-          } else {
-            e_even = ev;
+          if (e > 0 && ((e - 1) & 1)) {
+            const int pb = (e - 1) >> 4, pr = (e - 1) & 15;
+            p_out[pb][pr >> 3][(pr >> 1) & 3] = pack_bf16(e_even, e_last);
+            asm volatile("" ::"v"(p_out[pb][pr >> 3][(pr >> 1) & 3]));  // not later than this slot
           }
+          if (e > 0 && !((e - 1) & 1)) e_even = e_last;
+          // (an empty statement that defines the reference operand here keeps the exponential from
+          // starting before this slot)
+          asm volatile("" : "+v"(mneg[b2]));
+          e_last = __builtin_amdgcn_exp2f(__builtin_fmaf(s_in[b2][r], c, mneg[b2]));
         }
       __builtin_amdgcn_sched_barrier(0);
     }
     ls[1] += e_last;
+    p_out[1][1][3] = pack_bf16(e_even, e_last);
     // a partial sum that is large or not a number (always on the very first block, whose reference
     // is -inf): take the true block maximum, raise the reference, rescale, and redo the block
     if (__builtin_amdgcn_ballot_w64(!(ls[0] <= kSumLimit) || !(ls[1] <= kSumLimit)) != 0) {
