@@ -188,3 +188,32 @@ def test_mfma_lint_flags_early_use_of_an_inline_mfma_result():
     assert len(mfma_lint.lint(head + mfma + "\tds_read_b128 v[28:31], v60\n")) == 1
     # compiler-issued MFMAs are the compiler's business
     assert mfma_lint.lint(head + "\tv_mfma_f32_32x32x16_bf16 v[16:31], v[0:3], v[4:7], v[16:31]\n\tv_mov_b32_e32 v1, v16\n") == []
+
+
+def test_backward_and_persistent_validation_without_a_device(A):
+    p = 0x1000
+
+    def bwd(q=p, ws=p, d=128, dtype=0, N=8, Hq=2, Hkv=1):
+        return A.attn_bwd(q, p, p, p, p, p, p, p, p, ws, 1, Hq, Hkv, N, d, 0, 0.5, dtype, stream=0, check=False)
+
+    assert bwd(q=None) == 1 and bwd(ws=None) == 1
+    assert bwd(N=0) == 2 and bwd(Hq=3, Hkv=2) == 2 and bwd(ws=p + 4) == 2
+    assert bwd(d=64) == 4                      # the backward covers head dimension 128 only
+    assert bwd(dtype=1) in (3, 4)              # and bf16 only
+    assert A.attn_bwd_workspace_bytes(2, 32, 8192) == 2 * 32 * 2 * 8192 * 4
+    assert A.attn_bwd_workspace_bytes(1, 1, 1) == 2 * 64 * 4 and A.attn_bwd_workspace_bytes(0, 1, 1) == 0
+
+    def pers(queue=p, dtype=0, d=128):
+        return A.attn_fwd_persistent(p, p, p, p, p, 1, 2, 1, 8, d, 0, 0.5, dtype, queue, stream=0, check=False)
+
+    assert pers(queue=None) == 1 and pers(queue=p + 64) == 2
+    assert pers(dtype=1) == 4 and pers(d=96) == 4
+    assert A.attn_persistent_queue_bytes() == 1024
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0 and "--gpus" in r.stderr and r.stdout.strip() == ""
