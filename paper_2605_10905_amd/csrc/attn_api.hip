@@ -14,7 +14,7 @@ constexpr float kLog2e = 1.4426950408889634f;
 
 // all variant tables, concatenated; the first match for (dtype, d) is the default
 typedef const AttnVariant* (*VariantTable)(int*);
-const VariantTable kTables[] = {attn_bf16_sp_variants, attn_bf16_w16_variants, attn_bf16_pp_variants, attn_bf16_variants, attn_fp8_hy_variants, attn_fp8_cv_variants, attn_fp8_variants, attn_fp8_sp_variants, attn_bf16_q64_variants};
+const VariantTable kTables[] = {attn_bf16_sp_variants, attn_bf16_w16_variants, attn_bf16_pp_variants, attn_bf16_variants, attn_fp8_hy_variants, attn_fp8_cv_variants, attn_fp8_variants, attn_fp8_sp_variants, attn_bf16_q64_variants, attn_fp8_ht_variants};
 
 const AttnVariant* variant_at(int i) {
   if (i < 0) return nullptr;

@@ -22,6 +22,7 @@ namespace {
 
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2v;
 typedef __attribute__((ext_vector_type(8))) int i32x8;
+typedef __attribute__((ext_vector_type(2))) int i32x2;
 
 // 16 e4m3 bytes -> 16 bf16 (two 16-byte chunks), exact
 __device__ __forceinline__ void cvt16(const u32x4 in, u32x4& lo, u32x4& hi) {
@@ -52,18 +53,25 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
 // Scheduling-group pipeline of one pipelined step (the builtin wants literal constants, hence the
 // recursion): per MFMA its share of the plain vector work and of the 16 exponentials, and the two
 // LDS reads of the operand RA MFMAs ahead.
-template <int M, int NM, int NVALU>
+// VREADS: LDS reads per V fragment (two transposing reads, or one 128-bit read of a transposed tile);
+// a K fragment always takes two.  MFMAs 0 and 5 of a step are the score products.
+template <int M, int NM, int NVALU, int RA, int VREADS>
 __device__ __forceinline__ void hy_step_pipeline() {
   if constexpr (M < NM) {
+    constexpr int T = (M + RA) % NM;  // the MFMA whose operand is requested behind MFMA M
     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                         // MFMA
     __builtin_amdgcn_sched_group_barrier(0x002, (NVALU * (M + 1)) / NM - (NVALU * M) / NM, 0);  // VALU
     __builtin_amdgcn_sched_group_barrier(0x400, (16 * (M + 1)) / NM - (16 * M) / NM, 0);       // transcendental
-    __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);                                         // LDS read
-    hy_step_pipeline<M + 1, NM, NVALU>();
+    __builtin_amdgcn_sched_group_barrier(0x100, (T == 0 || T == 5) ? 2 : VREADS, 0);           // LDS read
+    hy_step_pipeline<M + 1, NM, NVALU, RA, VREADS>();
   }
 }
 
-template <int D, bool CAUSAL>
+// VT: the conversion pass also transposes.  The bf16 value tile then lies in LDS as V^T (one row per
+// head-dimension column, 64 keys in the order of the P V product's k-slots) and a V fragment is one
+// 128-bit read instead of two transposing 64-bit reads: an LDS read costs the LDS the same eight
+// cycles whatever its width, and the LDS instruction rate is what caps this kernel's matrix pipe.
+template <int D, bool CAUSAL, bool VT>
 __global__ void __launch_bounds__(512, 2) attn_fwd_fp8_hy_kernel(const AttnParams p) {
   static_assert(D == 128, "the staging layout assumes 128-byte fp8 rows");
   constexpr int BN = 64, NWAVES = 8, BM = NWAVES * 32, NT = NWAVES * 64;
@@ -122,7 +130,10 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_fp8_hy_kernel(const AttnParam
   // (LDS chunk c of a row holds the row's chunk c ^ swizzle); V goes to staging, unswizzled.
   const int st_row = tid >> 3, st_c = tid & 7;
   const uint32_t k_goff = st_row * INROWB + ((st_c ^ attn_swz_k<KROWB>(st_row)) << 4);
-  const uint32_t st_goff = st_row * INROWB + st_c * 16;
+  // VT: staged rows are read eight at a time (keys b + {0..3, 8..11}) by the 8-bit transposing read;
+  // LDS chunk c of staged row r holds the row's chunk c ^ fkey(r), so those eight land in different banks
+  auto fkey = [](int r) __attribute__((always_inline)) { return (r & 3) | (((r >> 3) & 1) << 2); };
+  const uint32_t st_goff = st_row * INROWB + (VT ? ((st_c ^ fkey(st_row)) << 4) : st_c * 16);
   const uint32_t lds_base = (uint32_t)(uintptr_t)smem;
   const uint32_t lds_wave = lds_base + w * 1024;
   const uint32_t lds_wave_stg = lds_base + STGBASE + w * 1024;
@@ -140,11 +151,39 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_fp8_hy_kernel(const AttnParam
   const uint32_t cv_v0 = VBASE + st_row * ROWB + (((2 * st_c) ^ attn_swz_v<ROWB>(st_row)) << 4);
   const uint32_t cv_v1 = VBASE + st_row * ROWB + (((2 * st_c + 1) ^ attn_swz_v<ROWB>(st_row)) << 4);
   const uint32_t st_self = STGBASE + tid * 16;  // this thread's chunk inside a staged tile
+  // VT: a 16-lane group transposes a block of 8 keys x 16 columns per round (two rounds cover the
+  // 64 blocks of a tile): lane s reads 8 bytes of staged key row e = s / 2, the hardware hands lane t
+  // the 8 keys of column t, which become one 16-byte chunk of row t of V^T.  Output chunk ch of a
+  // V^T row holds the keys of k-slot group ch = 4 (32-key half) + 2 kc + h in the order the S^T
+  // accumulator (and so the packed P^T operand) has them: 32 (ch / 4) + 16 kc + 4 h + {0..3, 8..11}.
+  uint32_t tr_src[2], tr_dst[2];
+#pragma unroll
+  for (int rnd = 0; rnd < 2; ++rnd) {
+    const int blk = rnd * 32 + w * 4 + (lane >> 4), ch = blk & 7, cg = blk >> 3;
+    const int s16 = lane & 15, e = s16 >> 1;
+    const int key = 32 * (ch >> 2) + 16 * ((ch >> 1) & 1) + 8 * (e >> 2) + 4 * (ch & 1) + (e & 3);
+    const int dcol = 16 * cg + s16;
+    tr_src[rnd] = STGBASE + key * INROWB + ((cg ^ fkey(key)) << 4) + ((s16 & 1) << 3);
+    tr_dst[rnd] = VBASE + dcol * 128 + ((ch ^ attn_swz_k<128>(dcol)) << 4);
+  }
   auto convert_v = [&](int stg, int slot) __attribute__((always_inline)) {
-    u32x4 lo, hi;
-    cvt16(*(const LDS_AS u32x4*)(smem + st_self + stg * STGTILE), lo, hi);
-    *(LDS_AS u32x4*)(smem + cv_v0 + slot * TILEB) = lo;
-    *(LDS_AS u32x4*)(smem + cv_v1 + slot * TILEB) = hi;
+    if constexpr (VT) {
+#pragma unroll
+      for (int rnd = 0; rnd < 2; ++rnd) {
+        const i32x2 t = __builtin_amdgcn_ds_read_tr8_b64_v2i32((LDS_AS i32x2*)(smem + tr_src[rnd] + stg * STGTILE));
+        u32x4 o;
+        o[0] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(t[0], 1.0f, false));
+        o[1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(t[0], 1.0f, true));
+        o[2] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(t[1], 1.0f, false));
+        o[3] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(t[1], 1.0f, true));
+        *(LDS_AS u32x4*)(smem + tr_dst[rnd] + slot * TILEB) = o;
+      }
+    } else {
+      u32x4 lo, hi;
+      cvt16(*(const LDS_AS u32x4*)(smem + st_self + stg * STGTILE), lo, hi);
+      *(LDS_AS u32x4*)(smem + cv_v0 + slot * TILEB) = lo;
+      *(LDS_AS u32x4*)(smem + cv_v1 + slot * TILEB) = hi;
+    }
   };
   // bundle b = key tile b+1 (the last tile again if there is none) and value tile b
   auto issue_bundle_k = [&](int b, int slot) __attribute__((always_inline)) { issue_k(min(b + 1, nt - 1), slot); };
@@ -190,15 +229,31 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_fp8_hy_kernel(const AttnParam
   }
   // block id = 2 * slot + (which 32-key half): byte offsets of that block in the K and in the V ring
   auto koff_of = [](auto bid) __attribute__((always_inline)) { return (bid >> 1) * KTILEB + (bid & 1) * KSUBB; };
-  auto voff_of = [](auto bid) __attribute__((always_inline)) { return (bid >> 1) * TILEB + (bid & 1) * SUBB; };
+  auto voff_of = [](auto bid) __attribute__((always_inline)) { return (bid >> 1) * TILEB; };  // slot of the value tile; bid & 1 is the half
   auto k_half = [&](int koff, int kk, int e) __attribute__((always_inline)) { return *(LDS_AS u32x4*)(smem + kaddr[kk][e] + koff); };
-  auto v_operand = [&](auto voff, int cb, int kc) __attribute__((always_inline)) {
-    const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(smem + vaddr[cb][0] + voff + kc * 16 * ROWB));
-    const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(smem + vaddr[cb][1] + voff + kc * 16 * ROWB));
-    s16x8 av;
-    av[0] = v0[0]; av[1] = v0[1]; av[2] = v0[2]; av[3] = v0[3];
-    av[4] = v1[0]; av[5] = v1[1]; av[6] = v1[2]; av[7] = v1[3];
-    return __builtin_bit_cast(u32x4, av);
+  // VT: fragment (cb, kc) of 32-key half kb: row 32 cb + qi of V^T, chunk 4 kb + 2 kc + h
+  uint32_t vtaddr[2][NCB][2];
+#pragma unroll
+  for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+      for (int kc = 0; kc < 2; ++kc) {
+        const int dcol = 32 * cb + qi;
+        vtaddr[kb][cb][kc] = VBASE + dcol * 128 + (((4 * kb + 2 * kc + h) ^ attn_swz_k<128>(dcol)) << 4);
+      }
+  // voff: offset of the value tile's ring slot; kb: which 32-key half
+  auto v_operand = [&](auto voff, int kb, int cb, int kc) __attribute__((always_inline)) {
+    if constexpr (VT) {
+      return *(LDS_AS u32x4*)(smem + vtaddr[kb][cb][kc] + voff);
+    } else {
+      const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(smem + vaddr[cb][0] + voff + kb * SUBB + kc * 16 * ROWB));
+      const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(smem + vaddr[cb][1] + voff + kb * SUBB + kc * 16 * ROWB));
+      s16x8 av;
+      av[0] = v0[0]; av[1] = v0[1]; av[2] = v0[2]; av[3] = v0[3];
+      av[4] = v1[0]; av[5] = v1[1]; av[6] = v1[2]; av[7] = v1[3];
+      return __builtin_bit_cast(u32x4, av);
+    }
   };
 
   // ---- streaming-softmax state ----------------------------------------------------------------
@@ -255,11 +310,11 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_fp8_hy_kernel(const AttnParam
       s = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(join(k_half(koff, kk, 0), k_half(koff, kk, 1)), qf[kk], s, 0, 0, 0, unit_scale, 0,
                                                           unit_scale);
   };
-  auto pv_block = [&](const u32x4 (&pk)[2], auto voff) __attribute__((always_inline)) {
+  auto pv_block = [&](const u32x4 (&pk)[2], int voff, int kb) __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < 2 * NCB; ++i) {
       const int cb = i % NCB, kc = i / NCB;
-      oacc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, v_operand(voff, cb, kc)),
+      oacc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kb ? v_operand(voff, 1, cb, kc) : v_operand(voff, 0, cb, kc)),
                                                          __builtin_bit_cast(bf16x8, pk[kc]), oacc[cb], 0, 0, 0);
     }
   };
@@ -317,7 +372,7 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_fp8_hy_kernel(const AttnParam
       o.y = k_half(koff_of(bid), m / 5, 1);
     } else {
       const int i = m - 1 - (m > 5);
-      o.x = v_operand(voff_of(bid), i % NCB, i / NCB);
+      o.x = v_operand(voff_of(bid), bid & 1, i % NCB, i / NCB);
       o.y = o.x;
     }
     return o;
@@ -356,7 +411,7 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_fp8_hy_kernel(const AttnParam
     }
     float ls = exp_block(s_in, p_out);
     constexpr int NVALU = 16 + 14 + 8 + 2;  // multiply-adds, adds, packs, final add + compare
-    hy_step_pipeline<0, NM, NVALU>();
+    hy_step_pipeline<0, NM, NVALU, RA, VT ? 1 : 2>();
     if (__builtin_amdgcn_ballot_w64(!(ls <= kSumLimit)) != 0) {
       float mx = fmaxf(s_in[0], s_in[1]);
 #pragma unroll
@@ -375,11 +430,11 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_fp8_hy_kernel(const AttnParam
 
   // the same step for blocks that may be masked or not visible to this wave (run-time offsets)
   auto step_any = [&](bool do_sm, int key0, bool do_mm, f32x16& s_in, f32x16& s_out, u32x4 (&p_out)[2], u32x4 (&p_pv)[2], int koff,
-                      int voff) __attribute__((always_inline)) {
+                      int voff, int kb) __attribute__((always_inline)) {
     if (do_sm) softmax_block(s_in, p_out, p_pv, key0, needs_mask(key0));
     if (do_mm) {
       qk_block(s_out, koff);
-      pv_block(p_pv, voff);
+      pv_block(p_pv, voff, kb);
     }
   };
 
@@ -390,14 +445,16 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_fp8_hy_kernel(const AttnParam
   for (int kk = 0; kk < NK8; ++kk)
 #pragma unroll
     for (int i = 0; i < 8; ++i) asm volatile("" ::"v"(qf[kk][i]));  // Q is in registers from here on
+  if (VT) attn_wg_barrier();  // the transposing pass reads what other threads staged
   convert_v(0, 0);
   staging_read_done();
   if (nt > 1) {
     issue_bundle_k(1, 1);
     stage_v(1, 1);
   }
-  if (nt > 2) stage_v(2, 0);
+  if (!VT && nt > 2) stage_v(2, 0);
   attn_wg_barrier();
+  if (VT && nt > 2) stage_v(2, 0);  // only now has every thread read staging slot 0
   if (wave_valid) {
     qk_block(s_b, (NSLOT - 1) * KTILEB);                         // S(0)
     softmax_block(s_b, p_b, p_a, 0, needs_mask(0));    // P(0) -> p_b (nothing pending yet)
@@ -407,6 +464,7 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_fp8_hy_kernel(const AttnParam
   if (nt > 1) {
     if (nt > 2) ATTN_WAIT_VMCNT(1);
     else ATTN_WAIT_VMCNT(0);
+    if (VT) attn_wg_barrier();
     convert_v(1, 1);
   }
   attn_wg_barrier();  // the K part of the last slot is empty again
@@ -440,9 +498,9 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_fp8_hy_kernel(const AttnParam
   };
   auto bundle_any = [&](int b, int slot) __attribute__((always_inline)) {
     const int k1 = (2 * b + 1) * 32, k2 = k1 + 32;
-    step_any(is_active(k1), k1, is_active(k1 - 32), s_a, s_b, p_a, p_b, slot * KTILEB, slot * TILEB);
+    step_any(is_active(k1), k1, is_active(k1 - 32), s_a, s_b, p_a, p_b, slot * KTILEB, slot * TILEB, 0);
     bundle_mid(b, slot >= 1 ? slot - 1 : NSLOT - 1);
-    step_any(is_active(k2), k2, is_active(k1), s_b, s_a, p_b, p_a, slot * KTILEB + KSUBB, slot * TILEB + SUBB);
+    step_any(is_active(k2), k2, is_active(k1), s_b, s_a, p_b, p_a, slot * KTILEB + KSUBB, slot * TILEB, 1);
   };
 
   // bundles 0 .. n_hot-1 touch only blocks (up to 2b+2) that every query of this wave sees in full
@@ -494,10 +552,10 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_fp8_hy_kernel(const AttnParam
   }
 }
 
-template <int D>
+template <int D, bool VT>
 int launch_hy(const AttnParams& p, int grid, hipStream_t stream) {
-  if (p.causal) hipLaunchKernelGGL((attn_fwd_fp8_hy_kernel<D, true>), dim3(grid), dim3(512), 0, stream, p);
-  else hipLaunchKernelGGL((attn_fwd_fp8_hy_kernel<D, false>), dim3(grid), dim3(512), 0, stream, p);
+  if (p.causal) hipLaunchKernelGGL((attn_fwd_fp8_hy_kernel<D, true, VT>), dim3(grid), dim3(512), 0, stream, p);
+  else hipLaunchKernelGGL((attn_fwd_fp8_hy_kernel<D, false, VT>), dim3(grid), dim3(512), 0, stream, p);
   return (int)hipGetLastError();
 }
 
@@ -505,7 +563,15 @@ int launch_hy(const AttnParams& p, int grid, hipStream_t stream) {
 
 const AttnVariant* attn_fp8_hy_variants(int* count) {
   static const AttnVariant table[] = {
-      {"fp8 d128 fp8-QK bf16-PV pipelined BM256 BN64", 1, 128, 256, 64, 512, 3 * 64 * 128 + 3 * 64 * 256 + 2 * 64 * 128, launch_hy<128>},
+      {"fp8 d128 fp8-QK bf16-PV pipelined BM256 BN64", 1, 128, 256, 64, 512, 3 * 64 * 128 + 3 * 64 * 256 + 2 * 64 * 128, launch_hy<128, false>},
+  };
+  *count = (int)(sizeof(table) / sizeof(table[0]));
+  return table;
+}
+
+const AttnVariant* attn_fp8_ht_variants(int* count) {
+  static const AttnVariant table[] = {
+      {"fp8 d128 fp8-QK bf16-PV transposed-V pipelined BM256 BN64", 1, 128, 256, 64, 512, 3 * 64 * 128 + 3 * 64 * 256 + 2 * 64 * 128, launch_hy<128, true>},
   };
   *count = (int)(sizeof(table) / sizeof(table[0]));
   return table;

@@ -63,3 +63,4 @@ const AttnVariant* attn_fp8_sp_variants(int* count);
 const AttnVariant* attn_fp8_cv_variants(int* count);
 const AttnVariant* attn_fp8_hy_variants(int* count);
 const AttnVariant* attn_bf16_q64_variants(int* count);
+const AttnVariant* attn_fp8_ht_variants(int* count);
