@@ -51,9 +51,9 @@ __device__ __forceinline__ float attn_sum_halves(float x) {
 // address lds_base + 16*i.  Inline assembly (uniform 64-bit base in SGPRs plus a per-lane
 // 32-bit offset, no VALU address arithmetic), so that the compiler does not serialise later
 // LDS reads of OTHER ring slots behind it; completion is tracked by hand with s_waitcnt
-// vmcnt before the barrier that publishes the slot.
+// vmcnt before the barrier that publishes the slot.  The statement overwrites m0 and says so.
 __device__ __forceinline__ void attn_lds_dma16(const void* sbase, uint32_t voff, uint32_t lds_base) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(voff), "s"(sbase));
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(voff), "s"(sbase) : "m0");
 }
 
 // s_waitcnt vmcnt(n) only (expcnt and lgkmcnt left alone)

@@ -57,14 +57,15 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
 // Scheduling-group pipeline of one pipelined step (the builtin wants literal constants, hence the
 // recursion): per MFMA its share of the plain vector work, of the 16 exponentials, and the LDS
 // reads of the operand RA MFMAs ahead (one 128-bit K read or two transposing V reads).
-template <int M, int NM, int RA, int NVALU>
+template <int M, int M1, int RA, int NVALU, int NEXP, int M0 = M>
 __device__ __forceinline__ void step_pipeline() {
-  if constexpr (M < NM) {
-    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                         // MFMA
-    __builtin_amdgcn_sched_group_barrier(0x002, (NVALU * (M + 1)) / NM - (NVALU * M) / NM, 0);  // VALU
-    __builtin_amdgcn_sched_group_barrier(0x400, 16 / NM, 0);                                   // transcendental
-    __builtin_amdgcn_sched_group_barrier(0x100, ((M + RA) & 1) ? 2 : 1, 0);                    // LDS read
-    step_pipeline<M + 1, NM, RA, NVALU>();
+  if constexpr (M < M1) {
+    constexpr int NS = M1 - M0;  // MFMAs of this scheduling region; each has NEXP exponentials
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                                        // MFMA
+    __builtin_amdgcn_sched_group_barrier(0x002, (NVALU * (M - M0 + 1)) / NS - (NVALU * (M - M0)) / NS, 0);    // VALU
+    __builtin_amdgcn_sched_group_barrier(0x400, NEXP, 0);                                                     // transcendental
+    __builtin_amdgcn_sched_group_barrier(0x100, ((M + RA) & 1) ? 2 : 1, 0);                                   // LDS read
+    step_pipeline<M + 1, M1, RA, NVALU, NEXP, M0>();
   }
 }
 
@@ -84,15 +85,13 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_bf16_sp_kernel(const AttnPara
   constexpr int NCH = ROWB / 16;    // 16-byte chunks per row
   constexpr int TILEB = BN * ROWB;  // bytes per K (or V) tile
   constexpr int SUBB = 32 * ROWB;   // bytes per 32-key block
-#ifndef ATTN_SP_NSLOT
-#define ATTN_SP_NSLOT 3
-#endif
-  constexpr int NSLOT = ATTN_SP_NSLOT;  // ring depth: bundles are requested NSLOT-1 ahead
+  constexpr int NSLOT = 3;  // ring depth: bundles are requested NSLOT-1 ahead
   constexpr int VBASE = NSLOT * TILEB;  // K parts of the slots first, then the V parts
   constexpr int NLD = BN * NCH / NT;    // direct-to-LDS loads per thread per tile
 #ifndef ATTN_RA
 #define ATTN_RA 4
 #endif
+
   constexpr int RA = ATTN_RA;           // operands are read from LDS this many MFMAs ahead
   static_assert(BN * NCH % NT == 0 && NLD >= 1, "tile must divide evenly over the workgroup");
   static_assert(NKK == 2 * NCB && RA >= 2 && RA <= 2 * NKK, "one PV step per QK^T step; read-ahead within a step");
@@ -170,6 +169,15 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_bf16_sp_kernel(const AttnPara
     }
   };
   const uint32_t lds_wave = (uint32_t)(uintptr_t)smem + w * 1024;
+  // Offsets of this thread's chunks inside the ragged last tile (rows past N-1 re-read row N-1),
+  // so that a tile load inside the pipelined step is one select away from the regular one.
+  uint32_t ld_koff_r[NLD], ld_voff_r[NLD];
+#pragma unroll
+  for (int it = 0; it < NLD; ++it) {
+    const uint32_t over = (uint32_t)max(0, (nt - 1) * BN + ld_row[it] - (N - 1)) * ROWB;
+    ld_koff_r[it] = ld_koff[it] - over;
+    ld_voff_r[it] = ld_voff[it] - over;
+  }
   // bundle b = key tile b+1 (the last tile again if there is none) and value tile b
   auto issue_bundle = [&](int b, int slot) __attribute__((always_inline)) {
     issue_tile(khead, min(b + 1, nt - 1), ld_koff, lds_wave + slot * TILEB);
@@ -337,29 +345,65 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_bf16_sp_kernel(const AttnPara
     }
     return ls0 + ls1;
   };
-  auto step_hot = [&](f32x16& s_in, f32x16& s_out, u32x4 (&p_out)[2], u32x4 (&p_pv)[2], auto off, auto offnext) __attribute__((always_inline)) {
+  // NSEG > 1 cuts the step into NSEG scheduling regions of NM/NSEG MFMAs each (each with its own
+  // share of the exponentials, sums and packs); between() runs at the cuts, which is where the
+  // producer role's tile loads go.
+  auto step_hot = [&](f32x16& s_in, f32x16& s_out, u32x4 (&p_out)[2], u32x4 (&p_pv)[2], auto off, auto offnext, auto nseg_tag, auto between) __attribute__((always_inline)) {
+    constexpr int NSEG = decltype(nseg_tag)::value, SEG = NM / NSEG;
+    static_assert(NM % NSEG == 0 && (16 / NSEG) % 2 == 0, "segments hold whole MFMAs and whole pairs of scores");
     u32x4 op[NM];
 #pragma unroll
     for (int m = 0; m < RA; ++m) op[m] = pre[m];
 #pragma unroll
     for (int r = 0; r < 16; ++r) s_out[r] = 0.f;
+    float ls0 = 0.f, ls1 = 0.f;
+    float e[16];
+    auto segment = [&](auto seg_tag) __attribute__((always_inline)) {
+      constexpr int SG = decltype(seg_tag)::value, M0 = SG * SEG, M1 = M0 + SEG;
+      constexpr int R0 = 16 * SG / NSEG, R1 = 16 * (SG + 1) / NSEG;  // scores exponentiated in this region
 #pragma unroll
-    for (int m = 0; m < NM; ++m) {
-      const int i = m >> 1;
-      if (m & 1)
-        oacc[i % NCB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, op[m]), __builtin_bit_cast(bf16x8, p_pv[i / NCB]),
-                                                                oacc[i % NCB], 0, 0, 0);
-      else
-        s_out = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, op[m]), qf[i], s_out, 0, 0, 0);
-      if (m + RA < NM) op[m + RA] = step_operand(off, m + RA);
-      else pre[m + RA - NM] = step_operand(offnext, m + RA - NM);
-    }
-    float ls = exp_block(s_in, p_out);
-    // pipeline: per MFMA one exponential, the plain vector work spread evenly, and the LDS
-    // reads of the operand RA MFMAs ahead (one 128-bit K read or two transposing V reads)
-    constexpr int NVALU = 16 + 14 + 8 + 2;  // multiply-adds, adds, packs, final add + compare
-    step_pipeline<0, NM, RA, NVALU>();
+      for (int m = M0; m < M1; ++m) {
+        const int i = m >> 1;
+        if (m & 1)
+          oacc[i % NCB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, op[m]), __builtin_bit_cast(bf16x8, p_pv[i / NCB]),
+                                                                  oacc[i % NCB], 0, 0, 0);
+        else
+          s_out = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, op[m]), qf[i], s_out, 0, 0, 0);
+        if (m + RA < NM) op[m + RA] = step_operand(off, m + RA);
+        else pre[m + RA - NM] = step_operand(offnext, m + RA - NM);
+      }
+#pragma unroll
+      for (int r = R0; r < R1; ++r) e[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s_in[r], c, -m_ref));
+#pragma unroll
+      for (int u = R0 / 2; u < R1 / 2; ++u) {
+        p_out[u >> 2][u & 3] = pack_bf16(e[2 * u], e[2 * u + 1]);
+        ls0 = u == 0 ? e[0] : ls0 + e[2 * u];
+        ls1 = u == 0 ? e[1] : ls1 + e[2 * u + 1];
+      }
+      // per MFMA one exponential, the plain vector work spread evenly, and the LDS reads of the
+      // operand RA MFMAs ahead (one 128-bit K read or two transposing V reads)
+      // multiply-adds, packs and adds of this region (the first pair starts the two sums, the
+      // last region adds them and compares)
+      constexpr int NVALU = (R1 - R0) + 3 * ((R1 - R0) / 2) - (SG == 0 ? 2 : 0) + (SG == NSEG - 1 ? 2 : 0);
+      if constexpr (SG == NSEG - 1) ls0 += ls1;
+      step_pipeline<M0, M1, RA, NVALU, 16 / NM>();
+      if constexpr (SG + 1 < NSEG) {
+        __builtin_amdgcn_sched_barrier(0);
+        between(SG + 1);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    };
+    between(0);
+    segment(ic<0>{});
+    if constexpr (NSEG > 1) segment(ic<1>{});
+    if constexpr (NSEG > 2) segment(ic<2>{});
+    if constexpr (NSEG > 3) segment(ic<3>{});
+    static_assert(NSEG <= 4, "at most four regions per step");
+    float ls = ls0;
     if (__builtin_amdgcn_ballot_w64(!(ls <= kSumLimit)) != 0) {
+      // the redo path "reads" the optimistic packs, so that they are computed inside the
+      // pipelined region above and not sunk below this branch into the common path's tail
+      asm volatile("" ::"v"(p_out[0]), "v"(p_out[1]));
       float mx = fmaxf(s_in[0], s_in[1]);
 #pragma unroll
       for (int r = 2; r < 16; ++r) mx = fmaxf(mx, s_in[r]);
@@ -417,11 +461,37 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_bf16_sp_kernel(const AttnPara
     attn_wg_barrier();
     if (b + NSLOT - 1 < nt) issue_bundle(b + NSLOT - 1, free_slot);
   };
+  auto no_loads = [](int) __attribute__((always_inline)) {};
+  // Producer role inside the pipelined step: the barrier between the two steps of an iteration
+  // frees a slot, and the loads of bundle b+NSLOT-1 into it are issued one at a time at the
+  // region cuts of the second step, between its operand reads, instead of in a burst behind the
+  // barrier (a burst keeps every wave of the workgroup off the matrix pipe at the same time).
+  // A bundle index past the end re-requests the last bundle into the free slot, which is never
+  // read again: the number of loads in flight per wave is then the same in every iteration.
   auto bundle_hot = [&](int b, auto slot_tag) __attribute__((always_inline)) {
     constexpr int SLOT = decltype(slot_tag)::value;
-    step_hot(s_a, s_b, p_a, p_b, ic<SLOT * TILEB>{}, ic<SLOT * TILEB + SUBB>{});
-    bundle_mid(b, (SLOT + NSLOT - 1) % NSLOT);
-    step_hot(s_b, s_a, p_b, p_a, ic<SLOT * TILEB + SUBB>{}, ic<((SLOT + 1) % NSLOT) * TILEB>{});
+    constexpr int FREE = (SLOT + NSLOT - 1) % NSLOT;
+    constexpr int NSEG = 2 * NLD < 2 ? 2 : 2 * NLD;
+    step_hot(s_a, s_b, p_a, p_b, ic<SLOT * TILEB>{}, ic<SLOT * TILEB + SUBB>{}, ic<1>{}, no_loads);
+    const int bl = min(b + NSLOT - 1, nt - 1);        // bundle to request
+    const int kt = min(bl + 1, nt - 1), vt = bl;      // its key and value tiles
+    const char* const kbase = khead + (size_t)kt * TILEB;
+    const char* const vbase = vhead + (size_t)vt * TILEB;
+    const bool k_ragged = (kt + 1) * BN > N, v_ragged = (vt + 1) * BN > N;
+    auto mid_and_loads = [&](int sg) __attribute__((always_inline)) {
+      if (sg == 0) {
+        if (NSLOT > 3) ATTN_WAIT_VMCNT(2 * NLD);  // bundle b+2 may stay in flight
+        else ATTN_WAIT_VMCNT(0);
+        attn_wg_barrier();
+      }
+#pragma unroll
+      for (int j = 0; j < 2 * NLD; ++j) {
+        if ((j < NSEG ? j : NSEG - 1) != sg) continue;
+        if (j < NLD) attn_lds_dma16(kbase, k_ragged ? ld_koff_r[j] : ld_koff[j], lds_wave + FREE * TILEB + j * NT * 16);
+        else attn_lds_dma16(vbase, v_ragged ? ld_voff_r[j - NLD] : ld_voff[j - NLD], lds_wave + VBASE + FREE * TILEB + (j - NLD) * NT * 16);
+      }
+    };
+    step_hot(s_b, s_a, p_b, p_a, ic<SLOT * TILEB + SUBB>{}, ic<((SLOT + 1) % NSLOT) * TILEB>{}, ic<NSEG>{}, mid_and_loads);
   };
   auto bundle_any = [&](int b, int slot) __attribute__((always_inline)) {
     const int k1 = (2 * b + 1) * 32, k2 = k1 + 32;
