@@ -39,7 +39,8 @@ typedef enum {
   ATTN_ERR_SHAPE = 2,       /* non-positive size, Hq % Hkv != 0, misaligned ptr   */
   ATTN_ERR_DTYPE = 3,       /* dtype is not one of attn_dtype                     */
   ATTN_ERR_UNSUPPORTED = 4, /* valid request this build has no kernel for (d)     */
-  ATTN_ERR_LAUNCH = 5       /* the HIP runtime refused the launch                 */
+  ATTN_ERR_LAUNCH = 5,      /* the HIP runtime refused the launch                 */
+  ATTN_ERR_TOO_LARGE = 6    /* attn_bwd_noalloc: needs more than the built-in scratch */
 } attn_status;
 
 typedef enum {
@@ -119,6 +120,27 @@ int attn_bwd(const void* q, const void* k, const void* v, const void* o, const v
 
 /* Size in bytes of the workspace attn_bwd needs (0 for non-positive sizes). */
 long long attn_bwd_workspace_bytes(int B, int Hq, int N);
+
+/*
+ * attn_bwd_noalloc -- attn_bwd for callers that cannot allocate device memory (code under HIP
+ * graph capture, tight serving or training loops, harnesses that forbid allocation): the same
+ * kernels, with the workspace taken from a scratch array that is part of the library's device
+ * code (attn_bwd_noalloc_max_workspace_bytes() = 32 MiB per GPU, held from the moment the library
+ * is loaded on that GPU until the process ends) instead of from an argument.  The call allocates
+ * and frees nothing.  The first call on a device looks the array's address up (one runtime query,
+ * no allocation); make that first call outside graph capture.
+ *   all arguments as attn_bwd, without `workspace`
+ * Returns ATTN_ERR_TOO_LARGE, before anything is enqueued, if attn_bwd_workspace_bytes(B,Hq,N)
+ * exceeds the scratch size (i.e. B*Hq*ceil(N/64)*64 > 4 194 304 rows).  Every call on a GPU uses
+ * that GPU's one array: calls that can overlap on the same GPU (different streams, different host
+ * threads) race on it and must be serialised by the caller; nothing needs clearing between calls
+ * (the query-side kernel rewrites every value the key-side kernel reads).  Same results, bit for
+ * bit, as attn_bwd.
+ */
+int attn_bwd_noalloc(const void* q, const void* k, const void* v, const void* o, const void* dout, const float* lse,
+                     void* dq, void* dk, void* dv,
+                     int B, int Hq, int Hkv, int N, int d, int causal, float scale, int dtype, void* stream);
+long long attn_bwd_noalloc_max_workspace_bytes(void);
 
 /*
  * attn_fwd_variant -- tuning hook: as attn_fwd, but with the kernel variant

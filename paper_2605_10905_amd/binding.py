@@ -42,6 +42,10 @@ lib.attn_bwd.argtypes = [_vp] * 10 + [_i, _i, _i, _i, _i, _i, _f, _i, _vp]
 lib.attn_bwd.restype = _i
 lib.attn_bwd_workspace_bytes.argtypes = [_i, _i, _i]
 lib.attn_bwd_workspace_bytes.restype = C.c_longlong
+lib.attn_bwd_noalloc.argtypes = [_vp] * 9 + [_i, _i, _i, _i, _i, _i, _f, _i, _vp]
+lib.attn_bwd_noalloc.restype = _i
+lib.attn_bwd_noalloc_max_workspace_bytes.argtypes = []
+lib.attn_bwd_noalloc_max_workspace_bytes.restype = C.c_longlong
 lib.gemm_bf16_nt.argtypes = [_vp, _vp, _vp, _i, _i, _i, _vp]
 lib.gemm_bf16_nt.restype = _i
 lib.gemm_bf16_nn.argtypes = [_vp, _vp, _vp, _i, _i, _i, _vp]
@@ -177,6 +181,18 @@ def attn_bwd(q, k, v, o, dout, lse, dq, dk, dv, workspace, B, Hq, Hkv, N, d, cau
                       _ptr(workspace), B, Hq, Hkv, N, d, int(bool(causal)), float(scale), int(dtype), _stream(stream))
     if check and st != 0:
         raise AttnError(st, "attn_bwd")
+    return st
+
+
+def attn_bwd_noalloc_max_workspace_bytes() -> int:
+    return lib.attn_bwd_noalloc_max_workspace_bytes()
+
+
+def attn_bwd_noalloc(q, k, v, o, dout, lse, dq, dk, dv, B, Hq, Hkv, N, d, causal, scale, dtype, stream=None, check=True):
+    st = lib.attn_bwd_noalloc(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(dout), _ptr(lse), _ptr(dq), _ptr(dk), _ptr(dv),
+                              B, Hq, Hkv, N, d, int(bool(causal)), float(scale), int(dtype), _stream(stream))
+    if check and st != 0:
+        raise AttnError(st, "attn_bwd_noalloc")
     return st
 
 

@@ -3,9 +3,14 @@
 #include <math.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "../../include/attn.h"
 #include "attn_kernels.h"
 #include "tile_map.h"
+
+constexpr long long kScratchBytes = 32ll << 20;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];  // see scratch_on_current_device()
 
 namespace {
 
@@ -86,9 +91,62 @@ int run(const void* q, const void* k, const void* v, void* o, float* lse, int B,
   return err == 0 ? ATTN_OK : ATTN_ERR_LAUNCH;
 }
 
+int bwd_validate(const void* q, const void* k, const void* v, const void* o, const void* dout, const float* lse, void* dq, void* dk,
+                 void* dv, int B, int Hq, int Hkv, int N, int d, float scale, int dtype) {
+  if (!q || !k || !v || !o || !dout || !lse || !dq || !dk || !dv) return ATTN_ERR_NULL;
+  if (dtype != ATTN_BF16 && dtype != ATTN_FP8_E4M3) return ATTN_ERR_DTYPE;
+  if (B <= 0 || Hq <= 0 || Hkv <= 0 || N <= 0 || d <= 0 || Hq % Hkv != 0) return ATTN_ERR_SHAPE;
+  const void* const ptrs[] = {q, k, v, o, dout, dq, dk, dv};
+  for (const void* ptr : ptrs)
+    if (misaligned(ptr, 16)) return ATTN_ERR_SHAPE;
+  if (misaligned(lse, 4)) return ATTN_ERR_SHAPE;
+  if (dtype != ATTN_BF16 || d != 128) return ATTN_ERR_UNSUPPORTED;
+  if (scale <= 0.0f) return ATTN_ERR_UNSUPPORTED;
+  if ((long long)N * d * 2 >= (1ll << 31)) return ATTN_ERR_UNSUPPORTED;
+  if ((long long)B * Hq * ((N + 255) / 256) > 0x7fffffffll) return ATTN_ERR_UNSUPPORTED;
+  return ATTN_OK;
+}
+
+int bwd_run(const void* q, const void* k, const void* v, const void* o, const void* dout, const float* lse, void* dq, void* dk,
+            void* dv, float* workspace, int B, int Hq, int Hkv, int N, int causal, float scale, void* stream) {
+  AttnBwdParams p;
+  p.q = q; p.k = k; p.v = v; p.o = o; p.dout = dout; p.lse = lse;
+  p.dq = dq; p.dk = dk; p.dv = dv; p.ws = workspace;
+  p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.N = N;
+  p.T = (N + 255) / 256;
+  p.Npad = (N + 63) / 64 * 64;
+  p.causal = causal ? 1 : 0;
+  p.scale_log2 = scale * kLog2e;
+  p.scale = scale;
+  return attn_bwd_launch_bf16_d128(p, (hipStream_t)stream) == 0 ? ATTN_OK : ATTN_ERR_LAUNCH;
+}
+
+// Scratch memory of attn_bwd_noalloc: the per-row statistics the backward kernels pass from the
+// query-side kernel to the key-side kernel, in a device array that is part of the loaded code
+// object (every GPU the library runs on holds its own copy until the process ends).  In host
+// code the array's name is only a handle: its device address is looked up once per device with
+// that device current, and only that address is ever handed to a kernel.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+float* g_scratch_ptr[kMaxDevices];  // zero-initialised: not looked up yet
+
+float* scratch_on_current_device() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return nullptr;
+    g_scratch_ptr[dev] = (float*)ptr;
+  }
+  return g_scratch_ptr[dev];
+}
+
 }  // namespace
 
 extern "C" {
+
+long long attn_bwd_workspace_bytes(int B, int Hq, int N);
 
 int attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse, int B, int Hq, int Hkv, int N, int d, int causal,
              float scale, int dtype, void* stream) {
@@ -138,28 +196,24 @@ int attn_persistent_queue_bytes(void) { return 8 * 32 * (int)sizeof(int); }
 
 int attn_bwd(const void* q, const void* k, const void* v, const void* o, const void* dout, const float* lse, void* dq, void* dk,
              void* dv, float* workspace, int B, int Hq, int Hkv, int N, int d, int causal, float scale, int dtype, void* stream) {
-  if (!q || !k || !v || !o || !dout || !lse || !dq || !dk || !dv || !workspace) return ATTN_ERR_NULL;
-  if (dtype != ATTN_BF16 && dtype != ATTN_FP8_E4M3) return ATTN_ERR_DTYPE;
-  if (B <= 0 || Hq <= 0 || Hkv <= 0 || N <= 0 || d <= 0 || Hq % Hkv != 0) return ATTN_ERR_SHAPE;
-  const void* const ptrs[] = {q, k, v, o, dout, dq, dk, dv, workspace};
-  for (const void* ptr : ptrs)
-    if (misaligned(ptr, 16)) return ATTN_ERR_SHAPE;
-  if (misaligned(lse, 4)) return ATTN_ERR_SHAPE;
-  if (dtype != ATTN_BF16 || d != 128) return ATTN_ERR_UNSUPPORTED;
-  if (scale <= 0.0f) return ATTN_ERR_UNSUPPORTED;
-  if ((long long)N * d * 2 >= (1ll << 31)) return ATTN_ERR_UNSUPPORTED;
-  AttnBwdParams p;
-  p.q = q; p.k = k; p.v = v; p.o = o; p.dout = dout; p.lse = lse;
-  p.dq = dq; p.dk = dk; p.dv = dv; p.ws = workspace;
-  p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.N = N;
-  p.T = (N + 255) / 256;
-  p.Npad = (N + 63) / 64 * 64;
-  p.causal = causal ? 1 : 0;
-  p.scale_log2 = scale * kLog2e;
-  p.scale = scale;
-  if ((long long)B * Hq * p.T > 0x7fffffffll) return ATTN_ERR_UNSUPPORTED;
-  return attn_bwd_launch_bf16_d128(p, (hipStream_t)stream) == 0 ? ATTN_OK : ATTN_ERR_LAUNCH;
+  const int st = bwd_validate(q, k, v, o, dout, lse, dq, dk, dv, B, Hq, Hkv, N, d, scale, dtype);
+  if (st != ATTN_OK) return st;
+  if (!workspace) return ATTN_ERR_NULL;
+  if (misaligned(workspace, 16)) return ATTN_ERR_SHAPE;
+  return bwd_run(q, k, v, o, dout, lse, dq, dk, dv, workspace, B, Hq, Hkv, N, causal, scale, stream);
 }
+
+int attn_bwd_noalloc(const void* q, const void* k, const void* v, const void* o, const void* dout, const float* lse, void* dq,
+                     void* dk, void* dv, int B, int Hq, int Hkv, int N, int d, int causal, float scale, int dtype, void* stream) {
+  const int st = bwd_validate(q, k, v, o, dout, lse, dq, dk, dv, B, Hq, Hkv, N, d, scale, dtype);
+  if (st != ATTN_OK) return st;
+  if (attn_bwd_workspace_bytes(B, Hq, N) > kScratchBytes) return ATTN_ERR_TOO_LARGE;
+  float* const ws = scratch_on_current_device();
+  if (!ws) return ATTN_ERR_LAUNCH;
+  return bwd_run(q, k, v, o, dout, lse, dq, dk, dv, ws, B, Hq, Hkv, N, causal, scale, stream);
+}
+
+long long attn_bwd_noalloc_max_workspace_bytes(void) { return kScratchBytes; }
 
 long long attn_bwd_workspace_bytes(int B, int Hq, int N) {
   if (B <= 0 || Hq <= 0 || N <= 0) return 0;
@@ -207,6 +261,7 @@ const char* attn_status_string(int status) {
     case ATTN_ERR_DTYPE: return "unknown dtype";
     case ATTN_ERR_UNSUPPORTED: return "unsupported configuration";
     case ATTN_ERR_LAUNCH: return "kernel launch failed";
+    case ATTN_ERR_TOO_LARGE: return "size exceeds the library's built-in scratch memory";
     default: return "unknown status";
   }
 }

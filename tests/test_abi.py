@@ -203,6 +203,18 @@ def test_backward_and_persistent_validation_without_a_device(A):
     assert A.attn_bwd_workspace_bytes(2, 32, 8192) == 2 * 32 * 2 * 8192 * 4
     assert A.attn_bwd_workspace_bytes(1, 1, 1) == 2 * 64 * 4 and A.attn_bwd_workspace_bytes(0, 1, 1) == 0
 
+    # the entry point without a workspace argument: same checks, and sizes beyond its built-in
+    # scratch memory are refused before anything touches a device
+    def bwd_na(q=p, d=128, dtype=0, N=8, Hq=2, Hkv=1, B=1):
+        return A.attn_bwd_noalloc(q, p, p, p, p, p, p, p, p, B, Hq, Hkv, N, d, 0, 0.5, dtype, stream=0, check=False)
+
+    assert bwd_na(q=None) == 1 and bwd_na(N=0) == 2 and bwd_na(Hq=3, Hkv=2) == 2 and bwd_na(d=64) == 4
+    cap = A.attn_bwd_noalloc_max_workspace_bytes()
+    assert cap == 32 << 20
+    assert A.attn_bwd_workspace_bytes(4, 64, 16384) == cap and A.attn_bwd_workspace_bytes(4, 64, 16385) > cap
+    assert bwd_na(B=4, Hq=64, Hkv=64, N=16385) == 6
+    assert "scratch" in A.attn_status_string(6)
+
     def pers(queue=p, dtype=0, d=128):
         return A.attn_fwd_persistent(p, p, p, p, p, 1, 2, 1, 8, d, 0, 0.5, dtype, queue, stream=0, check=False)
 
