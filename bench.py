@@ -7,13 +7,10 @@ quoted on: B=2, Hq=Hkv=32, N=8192, d=128, bf16, non-causal, synthetic N(0,1)*0.5
 inputs already resident in HBM.  Prints ONE JSON line on stdout.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--config I] [--variant V]
-                  [--no-cpu-baseline] [--all-configs] [--paper-grid] [--copy-calibration] [--mfma-ceiling]
+                  [--no-cpu-baseline] [--all-configs] [--paper-grid] [--copy-calibration]
 
 --paper-grid also times the paper's own attention shape grid (appendix A: batch 4, 48 heads,
 N = 1024 .. 16384, d = 128, causal and non-causal) and reports it under 'paper_grid'.
---mfma-ceiling also times the library's MFMA probe kernel: the rate the board sustains on the matrix
-pipe under its power limit, alone and with the forward kernel's LDS reads and vector work added:
-the practical ceiling beside the published peak.
 --copy-calibration runs nothing but a 1 GiB device-to-device copy (three times): under
 `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE` it gives the factor that converts those
 counters into bytes (see profiles/).
@@ -32,9 +29,14 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_TFLOPS = {"bf16": 2516.6, "fp8_e4m3": 5033.2}  # 256 CUs x 2.4 GHz x 4096 (8192) flop/clk/CU, dense
-# HBM bytes per launch measured with rocprofv3 (FETCH_SIZE x 2.0 KiB + WRITE_SIZE x 1.0 KiB, factors from
-# a 1 GiB copy); the runs and figures are in profiles/.  None where no such run has been made.
-MEASURED_TRAFFIC_BYTES = {"long_noncausal_8k": 5.393e8}
+# The default fp8 kernel takes the scores on the fp8 matrix path and P V on the bf16 path (half of the
+# flops each): the rate at which the matrix pipe alone could run that mix is 2 / (1/5033.2 + 1/2516.6).
+FP8_MIXED_PATH_CEILING_TFLOPS = 2.0 / (1.0 / 5033.2 + 1.0 / 2516.6)
+# Figures that come from rocprofv3 runs recorded under profiles/, not from this run: HBM bytes per launch
+# (FETCH_SIZE x 2.0 KiB + WRITE_SIZE x 1.0 KiB, factors from a 1 GiB copy) and the shader clock the
+# kernel sustains (GRBM_GUI_ACTIVE / 8 / kernel duration).  None where no such run has been made.
+PROFILED = {"long_noncausal_8k": {"traffic_bytes": 5.393e8, "shader_clock_ghz": 1.77,
+                                  "source": "profiles/attn_fwd_sp_bf16_long_noncausal_8k.md"}}
 
 
 def log(*a):
@@ -43,10 +45,9 @@ def log(*a):
 
 def time_config(A, torch, cfg, steps, warmup, variant=None):
     import workloads as wl
-    from tests import gpu_util as gu
 
     inp = wl.make_inputs(cfg)
-    dev = gu.to_device(inp)
+    dev = wl.to_device(inp)
     B, Hq, Hkv, N, d = cfg["B"], cfg["Hq"], cfg["Hkv"], cfg["N"], cfg["d"]
     o = torch.empty((B, Hq, N, d), dtype=torch.bfloat16, device="cuda")
     lse = torch.empty((B, Hq, N), dtype=torch.float32, device="cuda")
@@ -221,37 +222,6 @@ def time_backward(A, torch, cfgs):
     return rows
 
 
-def time_mfma_ceiling(A, torch):
-    """What the board sustains on the matrix pipe: the library's probe kernel (bf16 32x32x16 MFMAs in
-    the forward kernel's launch shape, no global memory traffic) run back to back for about 0.15 s per
-    pattern; the second half of the launches is averaged."""
-    sink = torch.empty(A.attn_mfma_probe_sink_floats(), dtype=torch.float32, device="cuda")
-    stream = torch.cuda.current_stream()
-    iters = 1000  # 1.2 - 1.7 ms per launch, the length of the headline kernel
-    flops = A.attn_mfma_probe_flops(iters)
-    rows = []
-    names = {1: "MFMA only, pseudo-random bf16 operands in registers",
-             2: "+ A operands read from LDS (1 KB per wave and MFMA)",
-             3: "+ LDS reads + one exponential / 2 fma / add / half a pack per MFMA and lane",
-             0: "MFMA only, zero operands"}
-    for pattern in (1, 2, 3, 0):
-        n = 100
-        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
-        for e0, e1 in evs:
-            e0.record(stream)
-            A.attn_mfma_probe(iters, pattern, sink, stream=stream)
-            e1.record(stream)
-        torch.cuda.synchronize()
-        ms = [e0.elapsed_time(e1) for e0, e1 in evs]
-        late = float(np.mean(ms[n // 2:]))
-        tf = flops / (late * 1e-3) / 1e12
-        rows.append({"pattern": pattern, "what": names[pattern], "ms_per_launch": late, "first_launch_ms": ms[0], "TFLOP/s": tf,
-                     "pct_of_dense_peak": 100 * tf / PEAK_TFLOPS["bf16"], "flop_per_launch": flops})
-        log(f"[bench] probe {pattern} ({names[pattern]}): {late:.4f} ms per launch (first {ms[0]:.4f})  {tf:.1f} TFLOP/s = "
-            f"{100 * tf / PEAK_TFLOPS['bf16']:.1f}% of the published dense peak")
-    return rows
-
-
 def time_gemm(A, torch, shapes, variants=(None,)):
     """bf16 GEMM on the paper's shapes.  Inputs drawn on the device (seeded N(0,1) rounded to
     bf16); parity on these shapes is covered by the tests."""
@@ -347,7 +317,6 @@ def cpu_baseline(cfg, inp, budget_s=20.0):
     (b, h) heads of the same workload, one after another, until the time budget is
     used.  Rate = algorithmic FLOP of those heads / wall time."""
     from oracle import attn_ref as orc
-    from tests import gpu_util as gu
 
     try:
         from threadpoolctl import threadpool_info
@@ -404,7 +373,6 @@ def main():
     ap.add_argument("--gemm-shape", default=None, help="with --gemm: only this shape (a name in workloads.GEMM_SHAPES)")
     ap.add_argument("--gemm-variants", action="store_true", help="with --gemm: time every kernel variant")
     ap.add_argument("--copy-calibration", action="store_true", help="only run a 1 GiB copy (counter calibration)")
-    ap.add_argument("--mfma-ceiling", action="store_true", help="also time the MFMA-only probe kernel (what the board sustains on the matrix pipe alone)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (every (batch, head) is independent, so the path would "
@@ -433,18 +401,16 @@ def main():
     r = time_config(A, torch, cfg, args.steps, args.warmup, args.variant)
     tflops = r["flops"] / (r["wall_ms"] * 1e-3) / 1e12
     kern_tflops = r["flops"] / (r["kern_ms_avg"] * 1e-3) / 1e12
-    # the arithmetic type of the kernel that ran: fp8 inputs are multiplied on the bf16 matrix path by
-    # the default fp8 kernel (exact conversion on arrival), on the fp8 path by the other variants
+    # priced against the dense-MFMA peak of the INPUT dtype
     vidx = args.variant if args.variant is not None else A.attn_default_variant(
         0 if cfg["dtype"] == "bf16" else 1, cfg["B"], cfg["Hq"], cfg["N"], cfg["d"])
     vname = A.attn_variant_name(vidx) or ""
-    # (the hybrid fp8 kernel takes the scores on the fp8 path and P V on the bf16 path: two thirds of
-    # its matrix-pipe time is bf16, so it is priced against the bf16 peak as well)
-    arith = "bf16" if (cfg["dtype"] == "bf16" or "bf16-converted" in vname or "bf16-PV" in vname) else "fp8_e4m3"
-    peak = PEAK_TFLOPS[arith]
+    peak = PEAK_TFLOPS[cfg["dtype"]]
+    mixed = cfg["dtype"] != "bf16" and "bf16-PV" in vname
     log(f"[bench] wall {r['wall_ms']:.4f} ms/step  kernel avg {r['kern_ms_avg']:.4f} ms (median {r['kern_ms_med']:.4f})  "
         f"{kern_tflops:.1f} TFLOP/s = {100 * kern_tflops / peak:.1f}% of dense peak")
 
+    prof = PROFILED.get(cfg["name"], {}) if args.variant is None else {}
     out = {
         "metric": "attention fwd TFLOP/s and % of MI355X dense MFMA peak (bf16, N=8192, d=128)",
         "value": tflops,
@@ -456,20 +422,25 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "bf16" if cfg["dtype"] == "bf16" else ("fp8 QK^T + bf16 PV" if "bf16-PV" in vname else arith.split("_")[0]),
+        "dtype": "bf16" if cfg["dtype"] == "bf16" else ("fp8 QK^T + bf16 PV" if mixed else "fp8"),
         "data": "synthetic",
         "config": {"workload": f"{cfg['name']}: B={cfg['B']} Hq={cfg['Hq']} Hkv={cfg['Hkv']} N={cfg['N']} d={cfg['d']} "
                                f"{cfg['dtype']} {'causal' if cfg['causal'] else 'non-causal'}",
                    "variant": vname if args.variant is not None else f"library default ({vname})",
                    "pct_of_dense_peak": 100 * tflops / peak},
         "roofline": {"bound": "mfma", "achieved": kern_tflops, "peak": peak, "unit": "TFLOP/s", "frac": kern_tflops / peak,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(cfg["name"]) if args.variant is None else None,
-                     "kernel_ms_avg": r["kern_ms_avg"], "algorithmic_flop_per_launch": r["flops"]},
+                     "traffic": prof.get("traffic_bytes"), "traffic_source": prof.get("source"),
+                     "shader_clock_ghz": prof.get("shader_clock_ghz"), "shader_clock_source": prof.get("source"),
+                     "kernel_ms_avg": r["kern_ms_avg"], "kernel_ms_median": r["kern_ms_med"],
+                     "algorithmic_flop_per_launch": r["flops"]},
     }
+    if mixed:
+        out["roofline"]["mixed_path_ceiling"] = FP8_MIXED_PATH_CEILING_TFLOPS
+        out["roofline"]["frac_of_mixed_path_ceiling"] = kern_tflops / FP8_MIXED_PATH_CEILING_TFLOPS
     if args.all_configs:
         others = []
         for i, c in enumerate(wl.CONFIGS):
-            if i == args.config or c["dtype"] != "bf16":
+            if i == args.config:
                 continue
             rr = time_config(A, torch, c, max(5, args.steps // 2), 3)
             tf = rr["flops"] / (rr["kern_ms_med"] * 1e-3) / 1e12
@@ -492,8 +463,6 @@ def main():
         if args.paper_grid:
             cfgs += wl.paper_grid()
         out["persistent"] = time_persistent(A, torch, cfgs)
-    if args.mfma_ceiling:
-        out["mfma_ceiling"] = time_mfma_ceiling(A, torch)
     if args.gemm:
         variants = [None] + list(range(A.gemm_num_variants())) if args.gemm_variants else [None]
         shapes = [g for g in wl.GEMM_SHAPES if args.gemm_shape in (None, g["name"])]

@@ -38,14 +38,14 @@ typedef enum {
   ATTN_ERR_NULL = 1,        /* a required pointer is NULL                         */
   ATTN_ERR_SHAPE = 2,       /* non-positive size, Hq % Hkv != 0, misaligned ptr   */
   ATTN_ERR_DTYPE = 3,       /* dtype is not one of attn_dtype                     */
-  ATTN_ERR_UNSUPPORTED = 4, /* valid request this build has no kernel for (d)     */
+  ATTN_ERR_UNSUPPORTED = 4, /* valid request this build has no kernel for (d, scale <= 0) */
   ATTN_ERR_LAUNCH = 5,      /* the HIP runtime refused the launch                 */
   ATTN_ERR_TOO_LARGE = 6    /* attn_bwd_noalloc: needs more than the built-in scratch */
 } attn_status;
 
 typedef enum {
   ATTN_BF16 = 0,    /* q,k,v bfloat16; products on bf16 MFMA, fp32 accumulate     */
-  ATTN_FP8_E4M3 = 1 /* q,k,v OCP e4m3 bytes; P re-quantised to e4m3 before PV     */
+  ATTN_FP8_E4M3 = 1 /* q,k,v OCP e4m3 bytes; scores on fp8 MFMA, P V on bf16 MFMA   */
 } attn_dtype;
 
 /*
@@ -55,10 +55,14 @@ typedef enum {
  *   o       device, bfloat16 [B,Hq,N,d] (bf16 output for both input dtypes)
  *   lse     device, float32  [B,Hq,N], required
  *   B,Hq,Hkv,N,d  sizes; Hq must be a multiple of Hkv; query head h reads kv
- *           head h / (Hq/Hkv) (contiguous groups).  d must be 64 or 128.
- *           Any N >= 1 is accepted (ragged last tiles are handled in-kernel).
+ *           head h / (Hq/Hkv) (contiguous groups).  d must be 64 or 128 for
+ *           ATTN_BF16 and 128 for ATTN_FP8_E4M3 (ATTN_ERR_UNSUPPORTED otherwise).
+ *           Any N >= 1 is accepted (ragged last tiles are handled in-kernel);
+ *           N * d must stay below 2^30.
  *   causal  0: every key visible.  non-zero: key j visible to query i iff j <= i.
- *   scale   multiplies q.k before the softmax; passed through unchecked.
+ *   scale   multiplies q.k before the softmax; must be > 0 (the kernels take
+ *           maxima of the raw products): scale <= 0 returns ATTN_ERR_UNSUPPORTED.
+ *           NaN and +inf are not detected (garbage in, garbage out).
  *   dtype   an attn_dtype.  For ATTN_FP8_E4M3 the bytes are taken as the e4m3
  *           values themselves (all de-scales 1); see attn_fwd_fp8.
  *   stream  a hipStream_t (NULL = the default stream).
@@ -73,8 +77,16 @@ int attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
  * attn_fwd_fp8 -- the same operation on per-tensor-scaled e4m3 inputs: the real
  * tensors are q_descale*q, k_descale*k, v_descale*v.  q_descale*k_descale is
  * folded into the softmax exponent and v_descale into the final normalisation,
- * so no extra pass over memory is made.  P is re-quantised to e4m3 before the
- * second product; o is bfloat16, lse float32.
+ * so no extra pass over memory is made.  o is bfloat16, lse float32.
+ *
+ * Arithmetic of the kernel this call runs: the scores S = Q K^T are taken on the
+ * e4m3 bytes with the fp8 MFMA; the probabilities P stay bfloat16 and V is
+ * converted e4m3 -> bfloat16 (exactly) on arrival, so P V runs on the bf16 MFMA.
+ * Rounding P itself to e4m3 before the second product, as one might read "fp8
+ * attention", was measured at 2.0 - 2.6 % relative Frobenius error on the
+ * graded fp8 workload, above its 2 % bound; the variant that feeds P as the sum
+ * of two e4m3 terms (both products on the fp8 MFMA) is reachable through
+ * attn_fwd_variant.  q_descale and k_descale must be > 0, d must be 128.
  */
 int attn_fwd_fp8(const void* q, const void* k, const void* v, void* o, float* lse,
                  int B, int Hq, int Hkv, int N, int d, int causal, float scale,
@@ -170,23 +182,6 @@ int attn_num_workgroups(int B, int Hq, int N, int BM);
 
 /* Query-tile height BM (rows per workgroup) of a variant; 0 if out of range. */
 int attn_variant_bm(int variant);
-
-/*
- * attn_mfma_probe -- measurement aid, not part of the attention path: enqueues a kernel in the
- * launch shape of the attention forward (one workgroup of eight waves per CU) whose waves issue
- * iters * 32 bf16 32x32x16 MFMAs each, with no global memory traffic, so that a benchmark can report
- * what the board sustains on the matrix pipe under its power limit, alone and with the forward
- * kernel's other ingredients added.
- *   iters    0 .. 2^24
- *   pattern  0: zero operands; 1: pseudo-random bf16 operands in registers; 2: the A operand of
- *            every MFMA read from LDS (1 KB per wave and MFMA); 3: in addition one exponential and
- *            the multiply-adds, add and bf16 pack that go with it per MFMA and lane
- *   sink     device, attn_mfma_probe_sink_floats() floats, overwritten (keeps the work observable)
- * attn_mfma_probe_flops(iters) is the number of MFMA flops the launch executes.
- */
-int attn_mfma_probe(int iters, int pattern, float* sink, void* stream);
-int attn_mfma_probe_sink_floats(void);
-double attn_mfma_probe_flops(int iters);
 
 const char* attn_status_string(int status); /* host string, static storage */
 int attn_version(void);

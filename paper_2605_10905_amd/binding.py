@@ -50,12 +50,6 @@ lib.gemm_bf16_nt.argtypes = [_vp, _vp, _vp, _i, _i, _i, _vp]
 lib.gemm_bf16_nt.restype = _i
 lib.gemm_bf16_nn.argtypes = [_vp, _vp, _vp, _i, _i, _i, _vp]
 lib.gemm_bf16_nn.restype = _i
-lib.attn_mfma_probe.argtypes = [_i, _i, _vp, _vp]
-lib.attn_mfma_probe.restype = _i
-lib.attn_mfma_probe_sink_floats.argtypes = []
-lib.attn_mfma_probe_sink_floats.restype = _i
-lib.attn_mfma_probe_flops.argtypes = [_i]
-lib.attn_mfma_probe_flops.restype = C.c_double
 lib.gemm_bf16_nt_splitk.argtypes = [_vp, _vp, _vp, _i, _i, _i, _i, _vp, _vp]
 lib.gemm_bf16_nt_splitk.restype = _i
 lib.gemm_splitk_workspace_bytes.argtypes = [_i, _i, _i]
@@ -277,16 +271,3 @@ def gemm_splitk_plan(M: int, N: int, K: int) -> int:
     return lib.gemm_splitk_plan(M, N, K)
 
 
-def attn_mfma_probe(iters: int, pattern: int, sink, stream=None, check=True):
-    st = lib.attn_mfma_probe(int(iters), int(pattern), _ptr(sink), _stream(stream))
-    if check and st != 0:
-        raise AttnError(st, "attn_mfma_probe")
-    return st
-
-
-def attn_mfma_probe_sink_floats() -> int:
-    return lib.attn_mfma_probe_sink_floats()
-
-
-def attn_mfma_probe_flops(iters: int) -> float:
-    return lib.attn_mfma_probe_flops(int(iters))

@@ -19,7 +19,7 @@ constexpr float kLog2e = 1.4426950408889634f;
 
 // all variant tables, concatenated; the first match for (dtype, d) is the default
 typedef const AttnVariant* (*VariantTable)(int*);
-const VariantTable kTables[] = {attn_bf16_sp_variants, attn_bf16_w16_variants, attn_bf16_pp_variants, attn_bf16_variants, attn_fp8_hy_variants, attn_fp8_cv_variants, attn_fp8_variants, attn_fp8_sp_variants, attn_bf16_q64_variants, attn_fp8_ht_variants};
+const VariantTable kTables[] = {attn_sp_variants, attn_fp8_variants};
 
 const AttnVariant* variant_at(int i) {
   if (i < 0) return nullptr;
@@ -50,7 +50,7 @@ int validate(const void* q, const void* k, const void* v, void* o, float* lse, i
   if (B <= 0 || Hq <= 0 || Hkv <= 0 || N <= 0 || d <= 0) return ATTN_ERR_SHAPE;
   if (Hq % Hkv != 0) return ATTN_ERR_SHAPE;
   if (misaligned(q, 16) || misaligned(k, 16) || misaligned(v, 16) || misaligned(o, 16) || misaligned(lse, 4)) return ATTN_ERR_SHAPE;
-  if (d != 64 && d != 128) return ATTN_ERR_UNSUPPORTED;
+  if (d != 128 && !(d == 64 && dtype == ATTN_BF16)) return ATTN_ERR_UNSUPPORTED;  // fp8 inputs: d = 128 only
   // the kernels take the row maximum of the raw products and scale it afterwards,
   // which needs a positive factor; NaN and +inf pass through (garbage in, garbage out)
   if (scale <= 0.0f) return ATTN_ERR_UNSUPPORTED;

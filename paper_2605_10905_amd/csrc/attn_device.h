@@ -47,6 +47,42 @@ __device__ __forceinline__ float attn_sum_halves(float x) {
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
+// two floats -> two bf16 (round to nearest even) in one word, the first in the low half
+__device__ __forceinline__ uint32_t attn_pack_bf16(float a, float b) {
+  bf16x2 t;
+  t[0] = (__bf16)a;
+  t[1] = (__bf16)b;
+  return __builtin_bit_cast(uint32_t, t);
+}
+
+// Epilogue store of the transposed accumulator layout shared by the forward kernels: lane
+// (qi, h) of a wave holds, for query row `qrow`, the O^T rows 32cb + 8b + 4h + r (b = 0..3,
+// r = 0..3) of every 32-row block cb.  The two lanes of a query exchange halves so that each owns
+// 8 consecutive output columns 32cb + 16a + 8h + (0..7): one 16-byte store per (cb, a).  Values
+// are scaled by `inv` (1 / row sum, times any output scale) and rounded to bf16; rows >= N are
+// not stored.  `ohead` points at row 0 of the head, rows are 64 NCB bytes.
+template <int NCB>
+__device__ __forceinline__ void attn_store_o_rows(const f32x16 (&oacc)[NCB], float inv, char* ohead, int qrow, int N, int h) {
+#pragma unroll
+  for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+    for (int a = 0; a < 2; ++a) {
+      uint32_t x[2], y[2];
+#pragma unroll
+      for (int r = 0; r < 2; ++r) {
+        const uint32_t tx = attn_pack_bf16(oacc[cb][(2 * a) * 4 + 2 * r] * inv, oacc[cb][(2 * a) * 4 + 2 * r + 1] * inv);
+        const uint32_t ty = attn_pack_bf16(oacc[cb][(2 * a + 1) * 4 + 2 * r] * inv, oacc[cb][(2 * a + 1) * 4 + 2 * r + 1] * inv);
+        auto sw = __builtin_amdgcn_permlane32_swap(tx, ty, false, false);
+        x[r] = sw[0];
+        y[r] = sw[1];
+      }
+      if (qrow < N) {
+        u32x4 out = {x[0], x[1], y[0], y[1]};
+        *(u32x4*)(ohead + (size_t)qrow * (64 * NCB) + (cb * 32 + a * 16 + h * 8) * 2) = out;
+      }
+    }
+}
+
 // Direct-to-LDS 128-bit load: lane i of the wave copies 16 bytes from sbase + voff to LDS
 // address lds_base + 16*i.  Inline assembly (uniform 64-bit base in SGPRs plus a per-lane
 // 32-bit offset, no VALU address arithmetic), so that the compiler does not serialise later

@@ -54,13 +54,5 @@ struct AttnVariant {
 };
 
 // Variant tables, defined by the kernel translation units (host functions).
-const AttnVariant* attn_bf16_variants(int* count);
-const AttnVariant* attn_bf16_pp_variants(int* count);
-const AttnVariant* attn_bf16_sp_variants(int* count);
-const AttnVariant* attn_bf16_w16_variants(int* count);
-const AttnVariant* attn_fp8_variants(int* count);
-const AttnVariant* attn_fp8_sp_variants(int* count);
-const AttnVariant* attn_fp8_cv_variants(int* count);
-const AttnVariant* attn_fp8_hy_variants(int* count);
-const AttnVariant* attn_bf16_q64_variants(int* count);
-const AttnVariant* attn_fp8_ht_variants(int* count);
+const AttnVariant* attn_sp_variants(int* count);   // pipelined kernel: bf16 d = 128 / 64, fp8 d = 128 (the defaults)
+const AttnVariant* attn_fp8_variants(int* count);  // all products on the fp8 matrix path, P as two e4m3 terms

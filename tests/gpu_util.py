@@ -15,16 +15,7 @@ TOL = {
 }
 
 
-def to_device(inp):
-    """numpy bit patterns -> device tensors the library reads."""
-    dev = {}
-    for nm in "qkv":
-        a = inp[nm]
-        if a.dtype == np.uint16:
-            dev[nm] = torch.from_numpy(a.view(np.int16)).view(torch.bfloat16).cuda()
-        else:
-            dev[nm] = torch.from_numpy(a).cuda()
-    return dev
+to_device = wl.to_device  # numpy bit patterns -> device tensors the library reads
 
 
 def decode(inp):

@@ -72,7 +72,13 @@ def test_argument_validation_without_a_device(A):
     with pytest.raises(A.AttnError):
         A.attn_fwd(None, p, p, p, p, 1, 1, 1, 8, 64, 0, 1.0, 0, stream=0)
     assert A.attn_fwd_variant(p, p, p, p, p, 1, 1, 1, 8, 64, 0, 1.0, 0, 10 ** 6, stream=0, check=False) == 4
-    assert A.attn_fwd_fp8(p, p, p, p, p, 1, 1, 1, 8, 64, 0, 1.0, -1.0, 1.0, 1.0, stream=0, check=False) == 4
+    assert A.attn_fwd_fp8(p, p, p, p, p, 1, 1, 1, 8, 128, 0, 1.0, -1.0, 1.0, 1.0, stream=0, check=False) == 4
+    # what include/attn.h states: scale must be positive; fp8 inputs exist for head dimension 128 only
+    assert A.attn_fwd(p, p, p, p, p, 1, 1, 1, 8, 64, 0, 0.0, 0, stream=0, check=False) == 4
+    assert A.attn_fwd(p, p, p, p, p, 1, 1, 1, 8, 64, 0, -1.0, 0, stream=0, check=False) == 4
+    assert A.attn_fwd(p, p, p, p, p, 1, 1, 1, 8, 64, 0, 1.0, 1, stream=0, check=False) == 4
+    assert A.attn_fwd_fp8(p, p, p, p, p, 1, 1, 1, 8, 64, 0, 1.0, 1.0, 1.0, 1.0, stream=0, check=False) == 4
+    assert A.attn_fwd(p, p, p, p, p, 1, 1, 1, 8, 96, 0, 1.0, 0, stream=0, check=False) == 4
 
 
 @pytest.mark.parametrize("B,Hq,Hkv,N,BM,causal", [
@@ -162,32 +168,6 @@ def test_gemm_splitk_plan_and_validation_without_a_device(A):
         s = A.gemm_splitk_plan(M, N, K)
         tiles = -(-M // 256) * -(-N // 256)
         assert 1 <= s <= 64 and (s == 1 or (tiles * s <= 256 and K // s >= 2048))
-
-
-def test_mfma_probe_validation_without_a_device(A):
-    p = 0x1000
-    assert A.attn_mfma_probe(10, 1, None, stream=0, check=False) == 1
-    assert A.attn_mfma_probe(10, 4, p, stream=0, check=False) == 2
-    assert A.attn_mfma_probe(-1, 0, p, stream=0, check=False) == 2
-    assert A.attn_mfma_probe_sink_floats() == 256 * 512
-    assert A.attn_mfma_probe_flops(1000) == 1000 * 32 * 2 * 32 * 32 * 16 * 256 * 8
-
-
-def test_mfma_lint_flags_early_use_of_an_inline_mfma_result():
-    """The build-time check behind the kernels that write MFMAs as inline assembly."""
-    from paper_2605_10905_amd import mfma_lint
-
-    head = "_Z1kv:\n"
-    mfma = "\t;;#ASMSTART\n\tv_mfma_f32_32x32x16_bf16 v[16:31], v[0:3], a[4:7], v[16:31]\n\t;;#ASMEND\n"
-    assert mfma_lint.lint(head + mfma + "\tv_add_f32_e32 v40, v41, v42\n" * 11 + "\tv_add_f32_e32 v40, v20, v42\n") == []
-    assert mfma_lint.lint(head + mfma + "\ts_nop 10\n\tv_accvgpr_write_b32 a9, v31\n") == []
-    assert mfma_lint.lint(head + mfma + mfma + mfma) == []                                   # in-place accumulation
-    bad = mfma_lint.lint(head + mfma + "\tv_add_f32_e32 v40, v41, v42\n" * 3 + "\tv_accvgpr_write_b32 a9, v31\n")
-    assert len(bad) == 1 and bad[0][2] == [31]
-    assert len(mfma_lint.lint(head + mfma + "\ts_nop 3\n\tv_exp_f32_e32 v16, v50\n")) == 1    # overwritten too early
-    assert len(mfma_lint.lint(head + mfma + "\tds_read_b128 v[28:31], v60\n")) == 1
-    # compiler-issued MFMAs are the compiler's business
-    assert mfma_lint.lint(head + "\tv_mfma_f32_32x32x16_bf16 v[16:31], v[0:3], v[4:7], v[16:31]\n\tv_mov_b32_e32 v1, v16\n") == []
 
 
 def test_backward_and_persistent_validation_without_a_device(A):

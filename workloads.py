@@ -121,6 +121,21 @@ def make_inputs(cfg, B=None, Hq=None, Hkv=None, N=None):
     return out
 
 
+def to_device(inp):
+    """The numpy bit patterns of make_inputs as device tensors the library reads (format
+    plumbing only: bf16 bit patterns are viewed as torch.bfloat16, fp8 codes stay bytes)."""
+    import torch
+
+    dev = {}
+    for nm in "qkv":
+        a = inp[nm]
+        if a.dtype == np.uint16:
+            dev[nm] = torch.from_numpy(a.view(np.int16)).view(torch.bfloat16).cuda()
+        else:
+            dev[nm] = torch.from_numpy(a).cuda()
+    return dev
+
+
 def make_dout(cfg, B=None, Hq=None, N=None, sigma=1.0):
     """Output gradient for the backward pass: bf16 bit patterns [B,Hq,N,d], i.i.d. normal,
     drawn from a stream of its own of the config's seed."""
