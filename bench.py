@@ -79,6 +79,8 @@ def time_config(A, torch, cfg, steps, warmup, variant=None):
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     kern_ms = [a.elapsed_time(b) for a, b in evs]
+    if os.environ.get("BENCH_TRACE"):
+        log("[bench] per-step kernel ms: " + " ".join(f"{x:.4f}" for x in kern_ms))
     flops = wl.algorithmic_flops(cfg)
     return dict(inp=inp, dev=dev, o=o, lse=lse, wall_ms=wall * 1e3 / steps, kern_ms_avg=float(np.mean(kern_ms)),
                 kern_ms_med=float(np.median(kern_ms)), flops=flops)

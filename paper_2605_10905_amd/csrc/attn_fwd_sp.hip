@@ -245,7 +245,6 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_sp_kernel(const AttnParams p)
       }
     }
   }
-  const int unit_scale = 0x7f7f7f7f;  // fp8 MFMA: E8M0 exponent 127 = 2^0 for both block scales
   if constexpr (!FP8) {
     if (nt > 1) {
       issue_k(min(2, nt - 1), 1);
@@ -299,7 +298,10 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_sp_kernel(const AttnParams p)
   auto qk_mfma = [&](const Operand& a, int kk, const f32x16& acc) __attribute__((always_inline)) {
     if constexpr (FP8) {
       const i32x8 av = i32x8{(int)a.x[0], (int)a.x[1], (int)a.x[2], (int)a.x[3], (int)a.y[0], (int)a.y[1], (int)a.y[2], (int)a.y[3]};
-      return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(av, qf[kk], acc, 0, 0, 0, unit_scale, 0, unit_scale);
+      // literal zero scale operands select the instruction without block scales (the scaled form
+      // is not recognised as a matrix instruction by the scheduling-group pipeline and would be
+      // left outside it, two dependent MFMAs back to back at the end of the step)
+      return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(av, qf[kk], acc, 0, 0, 0, 0, 0, 0);
     } else {
       return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a.x), qf[kk], acc, 0, 0, 0);
     }
@@ -542,14 +544,14 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_sp_kernel(const AttnParams p)
   // fp8 requests its key tile into it, converts its staged value tile (staging slot b mod 2) into
   // it, and stages the value tile of bundle b+3 where that of bundle b+1 was converted from.
   // A wave's LDS writes must have completed before it signals the barrier that publishes them.
-  auto publish_and_free = [&]() __attribute__((always_inline)) {
+  auto publish_and_free = [&](bool drain_lds) __attribute__((always_inline)) {
     ATTN_WAIT_VMCNT(0);
-    if constexpr (FP8) lds_ops_done();
+    if (FP8 && drain_lds) lds_ops_done();
     attn_wg_barrier();
   };
   // burst form, for the iterations that are not pipelined
   auto bundle_mid = [&](int b, int free_slot) __attribute__((always_inline)) {
-    publish_and_free();
+    publish_and_free(true);
     if (b + 2 < nt) {
       issue_k(min(b + 3, nt - 1), free_slot);
       if constexpr (FP8) convert_store(staged_chunk(b & 1), free_slot);
@@ -572,7 +574,9 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_sp_kernel(const AttnParams p)
     const int kt = min(b + 3, nt - 1), vt = min(b + 2, nt - 1);  // key and value tile of bundle b+2
     u32x4 staged;
     auto producer = [&](int sg) __attribute__((always_inline)) {
-      if (sg == 0) publish_and_free();
+      // (the conversion's LDS writes of the previous iteration have retired: LDS operations
+      // complete in order, and this wave has since waited for dozens of later operand reads)
+      if (sg == 0) publish_and_free(false);
       if constexpr (FP8) {
         if (sg == 0) {
           load_k(kt, FREE, 0);
