@@ -55,14 +55,14 @@ __device__ __forceinline__ uint32_t attn_pack_bf16(float a, float b) {
   return __builtin_bit_cast(uint32_t, t);
 }
 
-// Epilogue store of the transposed accumulator layout shared by the forward kernels: lane
-// (qi, h) of a wave holds, for query row `qrow`, the O^T rows 32cb + 8b + 4h + r (b = 0..3,
-// r = 0..3) of every 32-row block cb.  The two lanes of a query exchange halves so that each owns
-// 8 consecutive output columns 32cb + 16a + 8h + (0..7): one 16-byte store per (cb, a).  Values
-// are scaled by `inv` (1 / row sum, times any output scale) and rounded to bf16; rows >= N are
-// not stored.  `ohead` points at row 0 of the head, rows are 64 NCB bytes.
+// Epilogue of the transposed accumulator layout shared by the forward kernels: lane (qi, h) of a
+// wave holds, for its query row, the O^T rows 32cb + 8b + 4h + r (b = 0..3, r = 0..3) of every
+// 32-row block cb.  attn_pack_o_rows scales by `inv` (1 / row sum, times any output scale), rounds
+// to bf16 and lets the two lanes of a query exchange halves, so that each owns 8 consecutive
+// output columns 32cb + 16a + 8h + (0..7) in out[2cb + a]; attn_store_packed_o writes them with
+// one 16-byte store each, `dst` pointing at column 8h of the lane's output row.
 template <int NCB>
-__device__ __forceinline__ void attn_store_o_rows(const f32x16 (&oacc)[NCB], float inv, char* ohead, int qrow, int N, int h) {
+__device__ __forceinline__ void attn_pack_o_rows(const f32x16 (&oacc)[NCB], float inv, u32x4 (&out)[2 * NCB]) {
 #pragma unroll
   for (int cb = 0; cb < NCB; ++cb)
 #pragma unroll
@@ -76,11 +76,13 @@ __device__ __forceinline__ void attn_store_o_rows(const f32x16 (&oacc)[NCB], flo
         x[r] = sw[0];
         y[r] = sw[1];
       }
-      if (qrow < N) {
-        u32x4 out = {x[0], x[1], y[0], y[1]};
-        *(u32x4*)(ohead + (size_t)qrow * (64 * NCB) + (cb * 32 + a * 16 + h * 8) * 2) = out;
-      }
+      out[2 * cb + a] = u32x4{x[0], x[1], y[0], y[1]};
     }
+}
+template <int NCB>
+__device__ __forceinline__ void attn_store_packed_o(const u32x4 (&out)[2 * NCB], char* dst) {
+#pragma unroll
+  for (int i = 0; i < 2 * NCB; ++i) *(u32x4*)(dst + i * 32) = out[i];
 }
 
 // Direct-to-LDS 128-bit load: lane i of the wave copies 16 bytes from sbase + voff to LDS

@@ -80,16 +80,27 @@ __device__ __forceinline__ void step_pipeline() {
   }
 }
 
-// PERSIST: the launch has one workgroup per CU, and each takes query tiles from a queue until
-// it is drained.  The queue is 8 counters, one per XCD list of the static tile order (a tile
-// index wg belongs to list wg % 8, the XCD the static launch would run it on, and lists are
-// consumed heaviest tile first); a workgroup serves the list of the XCD it was dispatched to
-// and, when that is empty, the lists after it, so every tile is taken exactly once whatever the
-// dispatch order was.  This is the software stand-in for the paper's cluster launch control
-// (section 4.2): dynamic assignment of tiles to resident workgroups.
-template <int D, bool CAUSAL, bool PERSIST, bool FP8>
+// MODE says where a workgroup's query tiles come from.
+//   0: one tile per workgroup (the tile the workgroup id maps to).
+//   1: the launch has one workgroup per CU, and each takes tiles from a queue in device memory until
+//      it is drained.  The queue is 8 counters, one per XCD list of the static tile order (a tile
+//      index wg belongs to list wg % 8, the XCD the static launch would run it on, and lists are
+//      consumed heaviest tile first); a workgroup serves the list of the XCD it was dispatched to
+//      and, when that is empty, the lists after it, so every tile is taken exactly once whatever
+//      the dispatch order was.  This is the software stand-in for the paper's cluster launch
+//      control (section 4.2): dynamic assignment of tiles to resident workgroups.
+//   2: one workgroup per CU again, but each walks a list fixed by arithmetic: the tiles of its XCD's
+//      list are dealt to the XCD's workgroups in boustrophedon order (first to last, then last to
+//      first, ...), which balances lists sorted by weight (causal inputs) without a queue, without
+//      atomics and without any memory the library would have to own.
+// In modes 1 and 2 consecutive tiles of a workgroup overlap at the seam: the next tile's first
+// loads are requested as soon as every wave has left the ring, before the finished tile's output
+// is packed, and the packed output is stored only when the next tile's loads have been waited
+// for (loads and stores share one counter per wave, so a store in between would be waited for
+// as well).
+template <int D, bool CAUSAL, int MODE, bool FP8>
 __global__ void __launch_bounds__(512, 2) attn_fwd_sp_kernel(const AttnParams p) {
-  static_assert(!FP8 || (D == 128 && !PERSIST), "fp8 inputs: head dimension 128, static launch");
+  static_assert(!FP8 || (D == 128 && MODE != 1), "fp8 inputs: head dimension 128, no queue launch");
   constexpr int BN = 64, NWAVES = 8, BM = NWAVES * 32, NT = NWAVES * 64;
   constexpr int NCB = D / 32;                // 32-row blocks of O^T
   constexpr int ROWB = D * 2;                // bytes per bf16 row: V in the ring, O
@@ -126,42 +137,65 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_sp_kernel(const AttnParams p)
   const int qi = lane & 31;  // query column within the wave's 32-query block
   const int h = lane >> 5;   // which half of the k-slots / accumulator rows this lane holds
 
-  int lists_tried = 0;  // used by thread 0 only
-  for (;;) {
-  int wg = blockIdx.x;
-  if constexpr (PERSIST) {
-    if (tid == 0) {
-      int t = -1;
-      while (lists_tried < 8) {
-        const int x = (blockIdx.x + lists_tried) & 7;
-        const int s = atomicAdd(p.queue + x * 32, 1);
-        if (s * 8 + x < p.total) {
-          t = s * 8 + x;
-          break;
-        }
-        ++lists_tried;  // that list is drained (its counter keeps growing, which is harmless)
-      }
-      next_tile = t;
-    }
-    __syncthreads();  // also: every wave is done with the LDS ring of the previous tile
-    wg = __builtin_amdgcn_readfirstlane(next_tile);
-    __syncthreads();
-    if (wg < 0) break;
-  }
-  const AttnTileCoord tc = attn_tile_coord_impl(wg, p.B, p.Hq, p.Hkv, p.T, CAUSAL ? 1 : 0);
+  // ---- the tile this workgroup works on (re-assigned at every seam in modes 1 and 2) ------------
   const int N = p.N;
   const int G = p.Hq / p.Hkv;
-  const int hk = tc.hq / G;
-  const int q0 = tc.t * BM;
-  const int wq0 = q0 + w * 32;  // first query row of this wave
-  const bool wave_valid = wq0 < N;
-
-  const char* const qhead = (const char*)p.q + ((size_t)(tc.b * p.Hq + tc.hq) * N) * INB;
-  const char* const khead = (const char*)p.k + ((size_t)(tc.b * p.Hkv + hk) * N) * INB;
-  const char* const vhead = (const char*)p.v + ((size_t)(tc.b * p.Hkv + hk) * N) * INB;
-
-  const int kv_end = CAUSAL ? min(N, q0 + BM) : N;  // keys the workgroup visits
-  const int nt = (kv_end + BN - 1) / BN;            // 64-key tiles = bundles
+  int tile_b, tile_hq;              // batch and query head
+  int q0, wq0;                      // first query row of the tile / of this wave
+  bool wave_valid;
+  const char *qhead, *khead, *vhead;
+  int kv_end, nt;                   // keys the workgroup visits; 64-key tiles = bundles
+  int qrow, limit, wlast;           // this lane's query row, its last visible key, the wave's last row
+  auto set_tile = [&](int wg) __attribute__((always_inline)) {
+    const AttnTileCoord tc = attn_tile_coord_impl(wg, p.B, p.Hq, p.Hkv, p.T, CAUSAL ? 1 : 0);
+    tile_b = tc.b;
+    tile_hq = tc.hq;
+    const int hk = tc.hq / G;
+    q0 = tc.t * BM;
+    wq0 = q0 + w * 32;
+    wave_valid = wq0 < N;
+    qhead = (const char*)p.q + ((size_t)(tc.b * p.Hq + tc.hq) * N) * INB;
+    khead = (const char*)p.k + ((size_t)(tc.b * p.Hkv + hk) * N) * INB;
+    vhead = (const char*)p.v + ((size_t)(tc.b * p.Hkv + hk) * N) * INB;
+    kv_end = CAUSAL ? min(N, q0 + BM) : N;
+    nt = (kv_end + BN - 1) / BN;
+    qrow = wq0 + qi;
+    limit = CAUSAL ? min(qrow, N - 1) : (N - 1);
+    wlast = wq0 + 31;
+  };
+  // Next tile index of this workgroup, -1 when there is none.  Every thread calls it; in mode 1
+  // it contains the barrier after which no wave reads the ring of the finished tile any more.
+  int lists_tried = 0;  // mode 1, thread 0 only
+  int round = 0;        // mode 2: how many tiles this workgroup has taken
+  auto next_tile_index = [&]() __attribute__((always_inline)) {
+    if constexpr (MODE == 1) {
+      if (tid == 0) {
+        int t = -1;
+        while (lists_tried < 8) {
+          const int x = (blockIdx.x + lists_tried) & 7;
+          const int s = atomicAdd(p.queue + x * 32, 1);
+          if (s * 8 + x < p.total) {
+            t = s * 8 + x;
+            break;
+          }
+          ++lists_tried;  // that list is drained (its counter keeps growing, which is harmless)
+        }
+        next_tile = t;
+      }
+      __syncthreads();  // also: every wave is done with the LDS ring of the previous tile
+      const int wg = __builtin_amdgcn_readfirstlane(next_tile);
+      __syncthreads();
+      return wg;
+    } else {
+      // the grid is a multiple of 8 when the tile order has 8 lists (one per XCD), any size otherwise
+      const int lists = ((p.B * p.Hkv) & 7) == 0 ? 8 : 1;
+      const int per = (int)gridDim.x / lists;             // workgroups per list
+      const int x = (int)blockIdx.x % lists, s = (int)blockIdx.x / lists;
+      const int rank = round * per + ((round & 1) ? per - 1 - s : s);
+      ++round;
+      return rank * lists + x < p.total ? rank * lists + x : -1;
+    }
+  };
 
   // V rows in the ring: the swizzle of the transposing read; on the fp8 path rows r and r+4 also
   // differ in the lowest chunk bit, so that the conversion pass's 128-bit writes (eight rows per
@@ -181,7 +215,7 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_sp_kernel(const AttnParams p)
     const int r = s / NCHI, c = s % NCHI;
     ld_koff[it] = r * INB + ((c ^ attn_swz_k<INB>(r)) << 4);
     ld_voff[it] = r * INB + ((FP8 ? c : (c ^ swz_vring(r))) << 4);
-    const uint32_t over = (uint32_t)max(0, (nt - 1) * BN + r - (N - 1)) * INB;
+    const uint32_t over = (uint32_t)max(0, (N - 1) / BN * BN + r - (N - 1)) * INB;
     ld_koff_r[it] = ld_koff[it] - over;
     ld_voff_r[it] = ld_voff[it] - over;
   }
@@ -223,16 +257,16 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_sp_kernel(const AttnParams p)
   };
   auto lds_ops_done = [&]() __attribute__((always_inline)) { __builtin_amdgcn_s_waitcnt(0xC07F); };  // lgkmcnt(0)
 
-  // bundle b = key tile b+1 (the last tile again if there is none) and value tile b
-  issue_k(0, NSLOT - 1);  // key tile 0 borrows the K part of the last slot
-  issue_k(min(1, nt - 1), 0);
-  issue_v(0, 0);
-
-  // ---- Q operand (B operand of S^T = K Q^T) ------------------------------------------------------
-  // bf16: lane (qi,h) holds Q[row][16kk + 8h .. +7]; fp8: Q[row][64kk + 32h .. +31]
+  // ---- first requests of a tile: key tile 0, bundles 0 and 1, and the Q operand ------------------
+  // bundle b = key tile b+1 (the last tile again if there is none) and value tile b.
+  // Q is the B operand of S^T = K Q^T: bf16: lane (qi,h) holds Q[row][16kk + 8h .. +7];
+  // fp8: Q[row][64kk + 32h .. +31].
   using QFrag = std::conditional_t<FP8, i32x8, bf16x8>;
   QFrag qf[NKQ];
-  {
+  auto issue_prologue = [&]() __attribute__((always_inline)) {
+    issue_k(0, NSLOT - 1);  // key tile 0 borrows the K part of the last slot
+    issue_k(min(1, nt - 1), 0);
+    issue_v(0, 0);
     const int row = min(wq0 + qi, N - 1);
     const char* src = qhead + (size_t)row * INB + h * (FP8 ? 32 : 16);
 #pragma unroll
@@ -244,13 +278,13 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_sp_kernel(const AttnParams p)
         qf[kk] = *(const bf16x8*)(src + kk * 32);
       }
     }
-  }
-  if constexpr (!FP8) {
-    if (nt > 1) {
-      issue_k(min(2, nt - 1), 1);
-      issue_v(1, 1);
+    if constexpr (!FP8) {
+      if (nt > 1) {
+        issue_k(min(2, nt - 1), 1);
+        issue_v(1, 1);
+      }
     }
-  }
+  };
 
   // ---- LDS read addresses (slot 0, first 32-key block) -----------------------------------------
   // K fragment of k-step kk: lane (qi,h) reads key row qi, chunk 2kk + h (bf16) or chunks
@@ -309,21 +343,11 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_sp_kernel(const AttnParams p)
 
   // ---- streaming-softmax state ----------------------------------------------------------------
   f32x16 oacc[NCB];
-#pragma unroll
-  for (int cb = 0; cb < NCB; ++cb)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) oacc[cb][r] = 0.f;
-  float m_ref = -INFINITY;  // reference maximum, scaled log2 units
-  float l_run = 0.f;        // this lane's share of the row sum (halves are added at the end)
+  float m_ref;            // reference maximum, scaled log2 units
+  float l_run;            // this lane's share of the row sum (halves are added at the end)
   const float c = p.scale_log2;
-  const int qrow = wq0 + qi;
-  const int limit = CAUSAL ? min(qrow, N - 1) : (N - 1);  // last visible key of this lane's query
-  const int wlast = wq0 + 31;
-
   f32x16 s_a, s_b;        // S^T of two consecutive blocks (one consumed, one produced)
   u32x4 p_a[2], p_b[2];   // packed P^T of two consecutive blocks (one produced, one consumed)
-#pragma unroll
-  for (int i = 0; i < 2; ++i) p_a[i] = p_b[i] = u32x4{0, 0, 0, 0};
 
   // true maximum of a block in scaled log2 units (both lanes of a query column agree on it)
   auto block_max = [&](const f32x16& s) __attribute__((always_inline)) {
@@ -491,51 +515,6 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_sp_kernel(const AttnParams p)
     }
   };
 
-  // ---- prologue: block 0 ---------------------------------------------------------------------------
-  if constexpr (FP8) {
-    // everything requested so far has landed: convert value tile 0 into slot 0, request key tile 2
-    // and stage value tiles 1 and 2
-    ATTN_WAIT_VMCNT(0);
-#pragma unroll
-    for (int kk = 0; kk < NKQ; ++kk)
-#pragma unroll
-      for (int i = 0; i < 8; ++i) asm volatile("" ::"v"(qf[kk][i]));  // Q is in registers from here on
-    convert_store(staged_chunk(0), 0);
-    lds_ops_done();
-    if (nt > 1) {
-      issue_k(min(2, nt - 1), 1);
-      issue_v(1, 1);
-    }
-    if (nt > 2) issue_v(2, 0);
-  } else {
-    // key tile 0 (and Q) have landed once only the bundle loads issued after them are outstanding
-    if (nt > 1) ATTN_WAIT_VMCNT(4 * NLD);
-    else ATTN_WAIT_VMCNT(2 * NLD);
-#pragma unroll
-    for (int kk = 0; kk < NKQ; ++kk) asm volatile("" ::"v"(qf[kk]));  // Q is in registers from here on
-  }
-  attn_wg_barrier();
-  if (wave_valid) {
-    qk_block(s_b, (NSLOT - 1) * KTILEB);             // S(0)
-    softmax_block(s_b, p_b, p_a, 0, needs_mask(0));  // P(0) -> p_b (nothing pending yet)
-    qk_block(s_a, (NSLOT - 1) * KTILEB + KSUBB);     // S(1); ignored if block 1 is not visible
-  }
-  if constexpr (FP8) {
-    // bundle 1 has arrived once only value tile 2's load is outstanding: convert its value tile into slot 1
-    if (nt > 1) {
-      if (nt > 2) ATTN_WAIT_VMCNT(1);
-      else ATTN_WAIT_VMCNT(0);
-      convert_store(staged_chunk(1), 1);
-      lds_ops_done();
-    }
-  } else {
-    if (nt > 1) ATTN_WAIT_VMCNT(2 * NLD);
-    else ATTN_WAIT_VMCNT(0);
-  }
-  attn_wg_barrier();  // bundle 0 is full; the K part of the last slot is empty again
-#pragma unroll
-  for (int m = 0; m < RA; ++m) pre[m] = step_operand(ic<0>{}, m);  // first operands of the first pipelined step (block id 0)
-
   // ---- main loop over bundles ------------------------------------------------------------------------
   // Iteration b: exponentiate blocks 2b+1 and 2b+2, compute the scores of blocks 2b+2 and 2b+3
   // (key tile b+1), accumulate blocks 2b and 2b+1 (value tile b).  Between its two steps bundle
@@ -570,7 +549,7 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_sp_kernel(const AttnParams p)
     constexpr int SLOT = decltype(slot_tag)::value;
     constexpr int FREE = (SLOT + NSLOT - 1) % NSLOT;
     constexpr int NSEG = FP8 ? 2 : (2 * NLD < 2 ? 2 : 2 * NLD);
-    step_hot(s_a, s_b, p_a, p_b, ic<2 * SLOT>{}, ic<2 * SLOT + 1>{}, ic<1>{}, nothing);
+    step_hot(s_a, s_b, p_a, p_b, ic<2 * SLOT>{}, ic<2 * SLOT + 1>{}, ic<NSEG>{}, nothing);
     const int kt = min(b + 3, nt - 1), vt = min(b + 2, nt - 1);  // key and value tile of bundle b+2
     u32x4 staged;
     auto producer = [&](int sg) __attribute__((always_inline)) {
@@ -603,39 +582,161 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_sp_kernel(const AttnParams p)
     step_any(is_active(k2), k2, is_active(k1), s_b, s_a, p_b, p_a, slot * KTILEB + KSUBB, slot * TILEB + SUBB);
   };
 
-  // bundles 0 .. n_hot-1 touch only blocks (up to 2b+2) that every query of this wave sees in full
-  const int vis = CAUSAL ? min(wq0, N - 1) : N - 1;  // last key every query of the wave can see
-  const int n_hot = (wave_valid && vis >= 95) ? (vis - 95) / 64 + 1 : 0;
-  const int n_ring = n_hot - n_hot % NSLOT;  // whole turns of the ring, slot offsets as immediates
-  int b = 0;
-  for (; b < n_ring; b += NSLOT) {
-    bundle_hot(b, ic<0>{});
-    bundle_hot(b + 1, ic<1>{});
-    bundle_hot(b + 2, ic<2>{});
+  // ---- the tiles of this workgroup -----------------------------------------------------------------
+  int wg = (int)blockIdx.x;
+  if constexpr (MODE != 0) {
+    wg = next_tile_index();
+    if (wg < 0) return;
   }
-  // the last fully visible bundles (fewer than a turn), then the masked / partly visible ones
-  int slot = 0;
-  if (b < n_hot) { bundle_hot(b, ic<0>{}); ++b; slot = 1; }
-  if (b < n_hot) { bundle_hot(b, ic<1>{}); ++b; slot = 2; }
-  for (; b < nt; ++b) {
-    bundle_any(b, slot);
-    slot = slot == NSLOT - 1 ? 0 : slot + 1;
-  }
+  set_tile(wg);
+  issue_prologue();
+  // output of the previous tile, packed, waiting to be stored (modes 1 and 2)
+  u32x4 pend_o[2 * NCB];
+  float pend_lse = 0.f;
+  char* pend_o_ptr = nullptr;   // this lane's output row (null: row past the end)
+  float* pend_lse_ptr = nullptr;  // this lane's lse element (null: not this lane's to write)
+  bool pending = false;
+  for (;;) {
+    // fresh streaming-softmax state
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) oacc[cb][r] = 0.f;
+    m_ref = -INFINITY;
+    l_run = 0.f;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) p_a[i] = p_b[i] = u32x4{0, 0, 0, 0};
 
-  // ---- epilogue: O = acc / l (bf16), lse = (m + log2 l) * ln 2 ------------------------------------------
-  {
+    // ---- prologue: block 0 ---------------------------------------------------------------------------
+    if constexpr (FP8) {
+      // everything requested so far has landed: convert value tile 0 into slot 0, request key tile 2
+      // and stage value tiles 1 and 2
+      ATTN_WAIT_VMCNT(0);
+  #pragma unroll
+      for (int kk = 0; kk < NKQ; ++kk)
+  #pragma unroll
+        for (int i = 0; i < 8; ++i) asm volatile("" ::"v"(qf[kk][i]));  // Q is in registers from here on
+      convert_store(staged_chunk(0), 0);
+      lds_ops_done();
+      if (nt > 1) {
+        issue_k(min(2, nt - 1), 1);
+        issue_v(1, 1);
+      }
+      if (nt > 2) issue_v(2, 0);
+    } else {
+      // key tile 0 (and Q) have landed once only the bundle loads issued after them are outstanding
+      if (nt > 1) ATTN_WAIT_VMCNT(4 * NLD);
+      else ATTN_WAIT_VMCNT(2 * NLD);
+  #pragma unroll
+      for (int kk = 0; kk < NKQ; ++kk) asm volatile("" ::"v"(qf[kk]));  // Q is in registers from here on
+    }
+    attn_wg_barrier();
+    if (wave_valid) {
+      qk_block(s_b, (NSLOT - 1) * KTILEB);             // S(0)
+      softmax_block(s_b, p_b, p_a, 0, needs_mask(0));  // P(0) -> p_b (nothing pending yet)
+      qk_block(s_a, (NSLOT - 1) * KTILEB + KSUBB);     // S(1); ignored if block 1 is not visible
+    }
+    if constexpr (FP8) {
+      // bundle 1 has arrived once only value tile 2's load is outstanding: convert its value tile into slot 1
+      if (nt > 1) {
+        if (nt > 2) ATTN_WAIT_VMCNT(1);
+        else ATTN_WAIT_VMCNT(0);
+        convert_store(staged_chunk(1), 1);
+        lds_ops_done();
+      }
+    } else {
+      if (nt > 1) ATTN_WAIT_VMCNT(2 * NLD);
+      else ATTN_WAIT_VMCNT(0);
+    }
+    attn_wg_barrier();  // bundle 0 is full; the K part of the last slot is empty again
+    if constexpr (MODE != 0) {
+      // every load of this tile's prologue has been waited for: the previous tile's output may go
+      if (pending) {
+        if (pend_lse_ptr) *pend_lse_ptr = pend_lse;
+        if (pend_o_ptr) attn_store_packed_o<NCB>(pend_o, pend_o_ptr);
+      }
+    }
+  #pragma unroll
+    for (int m = 0; m < RA; ++m) pre[m] = step_operand(ic<0>{}, m);  // first operands of the first pipelined step (block id 0)
+
+
+    // bundles 0 .. n_hot-1 touch only blocks (up to 2b+2) that every query of this wave sees in full
+    const int vis = CAUSAL ? min(wq0, N - 1) : N - 1;  // last key every query of the wave can see
+    const int n_hot = (wave_valid && vis >= 95) ? (vis - 95) / 64 + 1 : 0;
+    const int n_ring = n_hot - n_hot % NSLOT;  // whole turns of the ring, slot offsets as immediates
+    int b = 0;
+    for (; b < n_ring; b += NSLOT) {
+      bundle_hot(b, ic<0>{});
+      bundle_hot(b + 1, ic<1>{});
+      bundle_hot(b + 2, ic<2>{});
+    }
+    // the last fully visible bundles (fewer than a turn), then the masked / partly visible ones
+    int slot = 0;
+    if (b < n_hot) { bundle_hot(b, ic<0>{}); ++b; slot = 1; }
+    if (b < n_hot) { bundle_hot(b, ic<1>{}); ++b; slot = 2; }
+    for (; b < nt; ++b) {
+      bundle_any(b, slot);
+      slot = slot == NSLOT - 1 ? 0 : slot + 1;
+    }
+
+
+    // ---- epilogue: O = acc / l (bf16), lse = (m + log2 l) * ln 2 ----------------------------------
     const float l = attn_sum_halves(l_run);
-    if (qrow < N && h == 0) p.lse[(size_t)(tc.b * p.Hq + tc.hq) * N + qrow] = (m_ref + __builtin_amdgcn_logf(l)) * 0.6931471805599453f;
-    attn_store_o_rows<NCB>(oacc, p.out_scale / l, (char*)p.o + ((size_t)(tc.b * p.Hq + tc.hq) * N) * ROWB, qrow, N, h);
-  }
-  if constexpr (!PERSIST) break;
+    const float lse_val = (m_ref + __builtin_amdgcn_logf(l)) * 0.6931471805599453f;
+    float* const lse_ptr = (qrow < N && h == 0) ? p.lse + (size_t)(tile_b * p.Hq + tile_hq) * N + qrow : nullptr;
+    char* const o_ptr = qrow < N ? (char*)p.o + ((size_t)(tile_b * p.Hq + tile_hq) * N + qrow) * ROWB : nullptr;
+    if constexpr (MODE == 0) {
+      if (lse_ptr) *lse_ptr = lse_val;
+      attn_pack_o_rows<NCB>(oacc, p.out_scale / l, pend_o);
+      if (o_ptr) attn_store_packed_o<NCB>(pend_o, o_ptr + h * 16);
+      break;
+    } else {
+      // seam: once no wave reads the ring any more, request the next tile's first loads, then
+      // pack this tile's output; it is stored when those loads have been waited for
+      if constexpr (MODE == 2) attn_wg_barrier();
+      const int nwg = next_tile_index();
+      if (nwg >= 0) {
+        set_tile(nwg);
+        issue_prologue();
+      }
+      attn_pack_o_rows<NCB>(oacc, p.out_scale / l, pend_o);
+      pend_lse = lse_val;
+      pend_lse_ptr = lse_ptr;
+      pend_o_ptr = o_ptr ? o_ptr + h * 16 : nullptr;
+      pending = true;
+      if (nwg < 0) {
+        if (pend_lse_ptr) *pend_lse_ptr = pend_lse;
+        if (pend_o_ptr) attn_store_packed_o<NCB>(pend_o, pend_o_ptr);
+        break;
+      }
+    }
   }  // tile loop
 }
 
+// resident workgroups of the list-walking launch: one per CU, rounded down to whole XCD shares
+int resident_workgroups() {
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+  return cus - cus % 8;
+}
+
+// Causal launches with at least three tiles per CU walk static tile lists (mode 2): the seams
+// between a workgroup's tiles hide part of what a workgroup pays per tile outside its main loop
+// (measured: +0.5 .. +4.5 %; with two tiles per CU the plain launch is 1 % faster).  Non-causal
+// launches run one tile per workgroup: in the list-walking instantiation the compiler's greedy
+// scheduling-group solver interleaves the pipelined step less well (5 % more cycles).
 template <int D, bool FP8>
 int launch_sp(const AttnParams& p, int grid, hipStream_t stream) {
-  if (p.causal) hipLaunchKernelGGL((attn_fwd_sp_kernel<D, true, false, FP8>), dim3(grid), dim3(512), 0, stream, p);
-  else hipLaunchKernelGGL((attn_fwd_sp_kernel<D, false, false, FP8>), dim3(grid), dim3(512), 0, stream, p);
+  const int resident = p.causal ? resident_workgroups() : 0;
+  if (p.causal && resident >= 8 && grid >= 3 * resident) {
+    AttnParams q = p;
+    q.total = grid;
+    hipLaunchKernelGGL((attn_fwd_sp_kernel<D, true, 2, FP8>), dim3(resident), dim3(512), 0, stream, q);
+  } else if (p.causal) {
+    hipLaunchKernelGGL((attn_fwd_sp_kernel<D, true, 0, FP8>), dim3(grid), dim3(512), 0, stream, p);
+  } else {
+    hipLaunchKernelGGL((attn_fwd_sp_kernel<D, false, 0, FP8>), dim3(grid), dim3(512), 0, stream, p);
+  }
   return (int)hipGetLastError();
 }
 
@@ -651,11 +752,11 @@ int attn_fwd_bf16_persistent_launch(const AttnParams& p, int d, int workgroups, 
   hipLaunchKernelGGL(attn_queue_reset_kernel, dim3(1), dim3(64), 0, stream, p.queue);
   const dim3 grid(workgroups < p.total ? workgroups : p.total);
   if (d == 128) {
-    if (p.causal) hipLaunchKernelGGL((attn_fwd_sp_kernel<128, true, true, false>), grid, dim3(512), 0, stream, p);
-    else hipLaunchKernelGGL((attn_fwd_sp_kernel<128, false, true, false>), grid, dim3(512), 0, stream, p);
+    if (p.causal) hipLaunchKernelGGL((attn_fwd_sp_kernel<128, true, 1, false>), grid, dim3(512), 0, stream, p);
+    else hipLaunchKernelGGL((attn_fwd_sp_kernel<128, false, 1, false>), grid, dim3(512), 0, stream, p);
   } else if (d == 64) {
-    if (p.causal) hipLaunchKernelGGL((attn_fwd_sp_kernel<64, true, true, false>), grid, dim3(512), 0, stream, p);
-    else hipLaunchKernelGGL((attn_fwd_sp_kernel<64, false, true, false>), grid, dim3(512), 0, stream, p);
+    if (p.causal) hipLaunchKernelGGL((attn_fwd_sp_kernel<64, true, 1, false>), grid, dim3(512), 0, stream, p);
+    else hipLaunchKernelGGL((attn_fwd_sp_kernel<64, false, 1, false>), grid, dim3(512), 0, stream, p);
   } else {
     return -1;
   }
