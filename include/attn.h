@@ -163,6 +163,11 @@ int attn_fwd_variant(const void* q, const void* k, const void* v, void* o, float
                      int B, int Hq, int Hkv, int N, int d, int causal, float scale,
                      int dtype, int variant, void* stream);
 
+/* The same hook for per-tensor-scaled e4m3 inputs: attn_fwd_fp8 with the kernel variant forced. */
+int attn_fwd_fp8_variant(const void* q, const void* k, const void* v, void* o, float* lse,
+                         int B, int Hq, int Hkv, int N, int d, int causal, float scale,
+                         float q_descale, float k_descale, float v_descale, int variant, void* stream);
+
 /* Number of kernel variants and a host string describing variant i (NULL if out of range). */
 int attn_num_variants(void);
 /* index of the variant attn_fwd / attn_fwd_fp8 run for this dtype and shape (-1: none) */

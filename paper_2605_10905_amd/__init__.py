@@ -10,7 +10,7 @@ The binding is imported on first attribute access, so that
 import importlib
 
 _NAMES = (
-    "ATTN_BF16", "ATTN_FP8_E4M3", "AttnError", "attn_bwd", "attn_bwd_noalloc", "attn_bwd_noalloc_max_workspace_bytes", "attn_bwd_workspace_bytes", "attn_default_variant", "attn_fwd", "attn_fwd_fp8", "attn_fwd_persistent", "attn_persistent_queue_bytes", "attn_fwd_variant", "attn_num_variants",
+    "ATTN_BF16", "ATTN_FP8_E4M3", "AttnError", "attn_bwd", "attn_bwd_noalloc", "attn_bwd_noalloc_max_workspace_bytes", "attn_bwd_workspace_bytes", "attn_default_variant", "attn_fwd", "attn_fwd_fp8", "attn_fwd_fp8_variant", "attn_fwd_persistent", "attn_persistent_queue_bytes", "attn_fwd_variant", "attn_num_variants",
     "attn_num_workgroups", "attn_status_string", "attn_tile_coord", "attn_variant_bm", "attn_variant_name", "attn_version",
     "gemm_bf16_nn", "gemm_bf16_nt", "gemm_bf16_nt_splitk", "gemm_bf16_nt_variant", "gemm_splitk_plan", "gemm_splitk_workspace_bytes", "gemm_num_variants", "gemm_num_workgroups", "gemm_tile_coord", "gemm_variant_kmult", "gemm_variant_name", "gemm_variant_tile",
     "lib", "lib_path",

@@ -38,6 +38,8 @@ lib.attn_fwd_persistent.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i,
 lib.attn_fwd_persistent.restype = _i
 lib.attn_persistent_queue_bytes.argtypes = []
 lib.attn_persistent_queue_bytes.restype = _i
+lib.attn_fwd_fp8_variant.argtypes = [_vp] * 5 + [_i] * 6 + [_f, _f, _f, _f, _i, _vp]
+lib.attn_fwd_fp8_variant.restype = _i
 lib.attn_bwd.argtypes = [_vp] * 10 + [_i, _i, _i, _i, _i, _i, _f, _i, _vp]
 lib.attn_bwd.restype = _i
 lib.attn_bwd_workspace_bytes.argtypes = [_i, _i, _i]
@@ -162,6 +164,15 @@ def attn_fwd_variant(q, k, v, o, lse, B, Hq, Hkv, N, d, causal, scale, dtype, va
                               float(scale), int(dtype), int(variant), _stream(stream))
     if check and st != 0:
         raise AttnError(st, "attn_fwd_variant")
+    return st
+
+
+def attn_fwd_fp8_variant(q, k, v, o, lse, B, Hq, Hkv, N, d, causal, scale, q_descale, k_descale, v_descale, variant, stream=None,
+                         check=True):
+    st = lib.attn_fwd_fp8_variant(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), B, Hq, Hkv, N, d, int(bool(causal)),
+                                  float(scale), float(q_descale), float(k_descale), float(v_descale), int(variant), _stream(stream))
+    if check and st != 0:
+        raise AttnError(st, "attn_fwd_fp8_variant")
     return st
 
 

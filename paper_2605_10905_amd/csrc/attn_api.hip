@@ -168,6 +168,16 @@ int attn_fwd_variant(const void* q, const void* k, const void* v, void* o, float
   return run(q, k, v, o, lse, B, Hq, Hkv, N, d, causal, scale, dtype, 1.0f, 1.0f, variant, stream);
 }
 
+int attn_fwd_fp8_variant(const void* q, const void* k, const void* v, void* o, float* lse, int B, int Hq, int Hkv, int N, int d,
+                         int causal, float scale, float q_descale, float k_descale, float v_descale, int variant, void* stream) {
+  if (!(q_descale > 0.0f) || !(k_descale > 0.0f)) return ATTN_ERR_UNSUPPORTED;
+  if (variant < 0 || variant >= total_variants()) {
+    int st = validate(q, k, v, o, lse, B, Hq, Hkv, N, d, scale, ATTN_FP8_E4M3);
+    return st != ATTN_OK ? st : ATTN_ERR_UNSUPPORTED;
+  }
+  return run(q, k, v, o, lse, B, Hq, Hkv, N, d, causal, scale, ATTN_FP8_E4M3, q_descale * k_descale, v_descale, variant, stream);
+}
+
 int attn_fwd_persistent(const void* q, const void* k, const void* v, void* o, float* lse, int B, int Hq, int Hkv, int N, int d,
                         int causal, float scale, int dtype, void* queue, void* stream) {
   int st = validate(q, k, v, o, lse, B, Hq, Hkv, N, d, scale, dtype);

@@ -120,12 +120,19 @@ def check_whole_head(inp, o, lse, b, h, label=""):
 
 
 # ---- backward --------------------------------------------------------------------------------
-# bf16 gradients: relative Frobenius error 5e-3 per tensor, and every element within
-# 2e-2 * max(1, max|reference|) (the gradients' scale varies with the mask and the length, so
-# the element-wise bound scales with the tensor's largest entry).  Below 64 keys every row is a
-# few-key row: there dP - delta cancels by the factor 1 - max(P), which amplifies the 2^-9
-# rounding of the stored bf16 O (delta = rowsum(dO * O)) by its inverse, so the Frobenius bound
-# is 1e-2 for those lengths; the element-wise bound is the same everywhere.
+# The target statement gives tolerances for the forward outputs only; the gradient bounds are
+# derived from the kernels' arithmetic.  Every rounding on the path is bf16 round-to-nearest with
+# relative RMS error 2^-9 / sqrt(3) = 1.1e-3: P (or dS) as a matrix operand, the stored forward O
+# inside delta = rowsum(dO * O), and the written gradient.  They add incoherently to about 2.3e-3
+# relative Frobenius error, which is what every well-conditioned case measures (2.3e-3 .. 2.5e-3
+# on the reduced and full-size configs).  Bounds: relative Frobenius error 5e-3 per tensor, and
+# every element within 2e-2 * max(1, max|reference|) (the gradients' scale varies with the mask
+# and the length, so the element-wise bound scales with the tensor's largest entry).
+# Where one key dominates a softmax row (rows of fewer than 64 keys, or inputs built that way),
+# dS = P * (dP - delta) cancels by the factor 1 - max(P): the 2^-9 rounding of the stored O that
+# enters delta is amplified by its inverse.  With max(P) = 0.9 the 2.3e-3 becomes about 6e-3
+# (measured: at most 5.8e-3 on the adversarial rows and the lengths below 64).  For those cases,
+# and only those, the Frobenius bound is 1e-2; the element-wise bound is the same everywhere.
 TOL_BWD = dict(rel_fro=5e-3, rel_fro_short=1e-2, short_n=64, max_abs_rel=2e-2)
 
 

@@ -216,6 +216,31 @@ def test_full_size_sampled(ci):
     assert bool(((oo <= hi + eps) & (oo >= lo - eps)).all())
 
 
+def test_config5_full_size_with_p_as_two_e4m3_terms():
+    """Config 5 as its wording has it (P re-quantised to e4m3 before the second product): the
+    variant that runs both products on the fp8 matrix path, P fed as the sum of two e4m3 terms,
+    at full size with the real per-tensor de-scales."""
+    import paper_2605_10905_amd as A
+
+    cfg = wl.CONFIGS[4]
+    var = next(i for i in range(A.attn_num_variants()) if A.attn_variant_name(i) == "fp8 d128 BM256 BN64")
+    print("config5, all-e4m3 variant: generating inputs", flush=True)
+    inp = wl.make_inputs(cfg)
+    dev = gu.to_device(inp)
+    B, Hq, Hkv, N, d = cfg["B"], cfg["Hq"], cfg["Hkv"], cfg["N"], cfg["d"]
+    o = torch.full((B, Hq, N, d), float("nan"), dtype=torch.bfloat16, device="cuda")
+    lse = torch.full((B, Hq, N), float("nan"), dtype=torch.float32, device="cuda")
+    ds = inp["descale"]
+    print("config5, all-e4m3 variant: launching", flush=True)
+    A.attn_fwd_fp8_variant(dev["q"], dev["k"], dev["v"], o, lse, B, Hq, Hkv, N, d, cfg["causal"], cfg["scale"], ds[0], ds[1], ds[2], var)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(555)
+    heads = [(0, 0), (B - 1, Hq - 1), (int(rng.integers(0, B)), int(rng.integers(0, Hq)))]
+    rows = [gu.sample_rows(N, 256, rng) for _ in heads]
+    print(f"config5, all-e4m3 variant: oracle on {sum(len(r) for r in rows)} sampled rows", flush=True)
+    print(gu.check_sampled(inp, o, lse, heads, rows, "config5, P as two e4m3 terms"), flush=True)
+
+
 # ---- the paper's own shape grid (d = 128; one batch element; all 48 heads at N = 1024, 8 heads
 # at the longer lengths so that drawing the inputs on the host stays within seconds) ------------
 @pytest.mark.parametrize("N,causal", [(1024, True), (1024, False), (4096, True), (16384, True), (16384, False)])
