@@ -66,11 +66,12 @@ def time_config(A, torch, cfg, steps, warmup, variant=None):
             A.attn_fwd_fp8(dev["q"], dev["k"], dev["v"], o, lse, B, Hq, Hkv, N, d, cfg["causal"], cfg["scale"], ds[0], ds[1],
                            ds[2], stream=stream)
 
+    # per-launch durations from events recorded on the launch stream (created before the warm-up so
+    # that nothing but the synchronisation sits between the warm-up and the timed steps)
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
     for _ in range(warmup):
         step()
     torch.cuda.synchronize()
-    # per-launch durations from events recorded on the launch stream
-    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
     t0 = time.perf_counter()
     for a, b in evs:
         a.record(stream)

@@ -197,10 +197,18 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_sp_kernel(const AttnParams p)
     }
   };
 
-  // V rows in the ring: the swizzle of the transposing read; on the fp8 path rows r and r+4 also
-  // differ in the lowest chunk bit, so that the conversion pass's 128-bit writes (eight rows per
-  // wave, two adjacent chunks per thread) spread evenly over the banks
-  auto swz_vring = [](int row) __attribute__((always_inline)) { return attn_swz_v<ROWB>(row) ^ (FP8 ? ((row >> 2) & 1) : 0); };
+  // V rows in the ring (256 bytes, 16 chunks): which physical chunk holds logical chunk `chunk`
+  // (columns 8 chunk .. 8 chunk + 7) of row `row`.  bf16: the XOR swizzle of the transposing read
+  // (four consecutive rows in different 64-byte groups).  fp8: the conversion pass writes the
+  // tile with 128-bit stores, which the LDS serves eight lanes (= one row's eight even or eight
+  // odd logical chunks) per cycle, without a second pass only if those eight lie in one 128-byte
+  // half of a bank line: the even logical chunks therefore fill the first half of a row and the
+  // odd ones the second, and rows are told apart inside the halves (bits 1-2), which keeps the
+  // transposing read's 32 lanes (4 rows x 64 bytes) on distinct banks as well.
+  auto v_chunk = [](int row, int chunk) __attribute__((always_inline)) {
+    if constexpr (FP8) return ((chunk >> 1) + 8 * (chunk & 1)) ^ ((row & 3) << 1);
+    else return chunk ^ attn_swz_v<ROWB>(row);
+  };
 
   // ---- producer role: direct-to-LDS tile loads ---------------------------------------------
   // Thread tid moves chunks tid, tid + NT, ... of a tile (16 bytes each).  K goes into the ring
@@ -214,7 +222,7 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_sp_kernel(const AttnParams p)
     const int s = it * NT + tid;
     const int r = s / NCHI, c = s % NCHI;
     ld_koff[it] = r * INB + ((c ^ attn_swz_k<INB>(r)) << 4);
-    ld_voff[it] = r * INB + ((FP8 ? c : (c ^ swz_vring(r))) << 4);
+    ld_voff[it] = r * INB + ((FP8 ? c : v_chunk(r, c)) << 4);
     const uint32_t over = (uint32_t)max(0, (N - 1) / BN * BN + r - (N - 1)) * INB;
     ld_koff_r[it] = ld_koff[it] - over;
     ld_voff_r[it] = ld_voff[it] - over;
@@ -240,8 +248,8 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_sp_kernel(const AttnParams p)
   // fp8: where this thread's 16 staged values (row tid / 8, bytes 16 (tid % 8) ..) go in a bf16
   // value tile: chunks 2 (tid % 8) and 2 (tid % 8) + 1 of that row
   const int st_row = tid >> 3, st_c = tid & 7;
-  const uint32_t cv_v0 = VBASE + st_row * ROWB + (((2 * st_c) ^ swz_vring(st_row)) << 4);
-  const uint32_t cv_v1 = VBASE + st_row * ROWB + (((2 * st_c + 1) ^ swz_vring(st_row)) << 4);
+  const uint32_t cv_v0 = VBASE + st_row * ROWB + (v_chunk(st_row, 2 * st_c) << 4);
+  const uint32_t cv_v1 = VBASE + st_row * ROWB + (v_chunk(st_row, 2 * st_c + 1) << 4);
   const uint32_t st_self = STGBASE + tid * 16;  // this thread's chunk inside a staged tile
   auto staged_chunk = [&](int stg) __attribute__((always_inline)) { return *(const LDS_AS u32x4*)(smem + st_self + stg * STGTILE); };
   auto convert_store = [&](const u32x4 in, int slot) __attribute__((always_inline)) {
@@ -305,7 +313,7 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_sp_kernel(const AttnParams p)
       for (int e = 0; e < 2; ++e) {
         const int key = 8 * e + 4 * h + (s >> 2);
         const int chunk = cb * 4 + chalf * 2 + ((s & 3) >> 1);
-        vaddr[cb][e] = VBASE + key * ROWB + ((chunk ^ swz_vring(key)) << 4) + ((s & 1) << 3);
+        vaddr[cb][e] = VBASE + key * ROWB + (v_chunk(key, chunk) << 4) + ((s & 1) << 3);
       }
   }
   // A block id names a 32-key block of the ring: 2 * slot + (which half of the slot's tiles)
