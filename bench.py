@@ -7,10 +7,13 @@ quoted on: B=2, Hq=Hkv=32, N=8192, d=128, bf16, non-causal, synthetic N(0,1)*0.5
 inputs already resident in HBM.  Prints ONE JSON line on stdout.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--config I] [--variant V]
-                  [--no-cpu-baseline] [--all-configs] [--paper-grid] [--copy-calibration]
+                  [--no-cpu-baseline] [--all-configs] [--paper-grid] [--copy-calibration] [--zero-operands]
 
 --paper-grid also times the paper's own attention shape grid (appendix A: batch 4, 48 heads,
 N = 1024 .. 16384, d = 128, causal and non-causal) and reports it under 'paper_grid'.
+--zero-operands also times the same launch on all-zero q, k, v (reported in 'zero_operands'): the
+same instruction stream with nothing toggling in the data paths, which the board runs at its full
+clock: the gap to the headline figure is what the power limit costs on random data.
 --copy-calibration runs nothing but a 1 GiB device-to-device copy (three times): under
 `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE` it gives the factor that converts those
 counters into bytes (see profiles/).
@@ -35,7 +38,7 @@ FP8_MIXED_PATH_CEILING_TFLOPS = 2.0 / (1.0 / 5033.2 + 1.0 / 2516.6)
 # Figures that come from rocprofv3 runs recorded under profiles/, not from this run: HBM bytes per launch
 # (FETCH_SIZE x 2.0 KiB + WRITE_SIZE x 1.0 KiB, factors from a 1 GiB copy) and the shader clock the
 # kernel sustains (GRBM_GUI_ACTIVE / 8 / kernel duration).  None where no such run has been made.
-PROFILED = {"long_noncausal_8k": {"traffic_bytes": 5.393e8, "shader_clock_ghz": 1.77,
+PROFILED = {"long_noncausal_8k": {"traffic_bytes": 5.393e8, "shader_clock_ghz": 1.65,
                                   "source": "profiles/attn_fwd_sp_bf16_long_noncausal_8k.md"}}
 
 
@@ -43,11 +46,14 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def time_config(A, torch, cfg, steps, warmup, variant=None):
+def time_config(A, torch, cfg, steps, warmup, variant=None, zero_operands=False):
     import workloads as wl
 
     inp = wl.make_inputs(cfg)
     dev = wl.to_device(inp)
+    if zero_operands:
+        for t in dev.values():
+            t.zero_()
     B, Hq, Hkv, N, d = cfg["B"], cfg["Hq"], cfg["Hkv"], cfg["N"], cfg["d"]
     o = torch.empty((B, Hq, N, d), dtype=torch.bfloat16, device="cuda")
     lse = torch.empty((B, Hq, N), dtype=torch.float32, device="cuda")
@@ -376,6 +382,8 @@ def main():
     ap.add_argument("--gemm-shape", default=None, help="with --gemm: only this shape (a name in workloads.GEMM_SHAPES)")
     ap.add_argument("--gemm-variants", action="store_true", help="with --gemm: time every kernel variant")
     ap.add_argument("--copy-calibration", action="store_true", help="only run a 1 GiB copy (counter calibration)")
+    ap.add_argument("--zero-operands", action="store_true",
+                    help="also time the same launch on all-zero inputs (same instructions, full clock; reported in 'zero_operands')")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (every (batch, head) is independent, so the path would "
@@ -440,6 +448,14 @@ def main():
     if mixed:
         out["roofline"]["mixed_path_ceiling"] = FP8_MIXED_PATH_CEILING_TFLOPS
         out["roofline"]["frac_of_mixed_path_ceiling"] = kern_tflops / FP8_MIXED_PATH_CEILING_TFLOPS
+    if args.zero_operands:
+        rz = time_config(A, torch, cfg, args.steps, args.warmup, args.variant, zero_operands=True)
+        tfz = rz["flops"] / (rz["kern_ms_avg"] * 1e-3) / 1e12
+        out["zero_operands"] = {"kernel_ms_avg": rz["kern_ms_avg"], "kernel_ms_median": rz["kern_ms_med"], "TFLOP/s": tfz,
+                                "pct_of_dense_peak": 100 * tfz / peak,
+                                "what": "the same launch on all-zero q, k, v: identical instruction stream, no data toggling"}
+        log(f"[bench] zero operands: kernel avg {rz['kern_ms_avg']:.4f} ms  {tfz:.1f} TFLOP/s = {100 * tfz / peak:.1f}% of dense peak")
+        del rz
     if args.all_configs:
         others = []
         for i, c in enumerate(wl.CONFIGS):
