@@ -189,7 +189,7 @@ def time_persistent(A, torch, cfgs):
 
 
 def time_backward(A, torch, cfgs):
-    """Backward pass (bf16, d = 128) on the given shapes: one step = attn_bwd (three kernels).
+    """Backward pass (bf16, d = 128 or 64) on the given shapes: one step = attn_bwd (two kernels).
     Inputs are drawn on the device (seeded N(0,1), rounded to bf16) and O, lse come from
     attn_fwd on them; parity on these shapes is covered by the tests.  TFLOP/s counts the five
     N x N x d products of the textbook backward (2.5 x the forward figure)."""
@@ -515,6 +515,8 @@ def main():
         cfgs = [c for c in wl.CONFIGS if c["dtype"] == "bf16" and c["d"] == 128 and (args.all_configs or c is cfg)]
         if args.paper_grid:
             cfgs += wl.paper_grid()
+        if args.extra_shapes:
+            cfgs += [c for c in wl.extra_shapes() if c["d"] == 64]
         out["backward"] = time_backward(A, torch, cfgs)
     if args.persistent:
         cfgs = [c for c in wl.CONFIGS if c["dtype"] == "bf16"]

@@ -121,7 +121,7 @@ int attn_persistent_queue_bytes(void);
  *   dk,dv         device, bfloat16 [B,Hkv,N,d], overwritten
  *   workspace     device, attn_bwd_workspace_bytes(B,Hq,N) bytes, 16-byte aligned, owned by the
  *                 caller; contents on entry are irrelevant, contents on return unspecified
- *   dtype         ATTN_BF16 only; d must be 128 (ATTN_ERR_UNSUPPORTED otherwise)
+ *   dtype         ATTN_BF16 only; d must be 128 or 64 (ATTN_ERR_UNSUPPORTED otherwise)
  *
  * Deterministic (no atomics).  Two kernels are enqueued on `stream`; the call returns without
  * synchronising.  Returns an attn_status; argument checks run before anything is enqueued.

@@ -100,7 +100,7 @@ int bwd_validate(const void* q, const void* k, const void* v, const void* o, con
   for (const void* ptr : ptrs)
     if (misaligned(ptr, 16)) return ATTN_ERR_SHAPE;
   if (misaligned(lse, 4)) return ATTN_ERR_SHAPE;
-  if (dtype != ATTN_BF16 || d != 128) return ATTN_ERR_UNSUPPORTED;
+  if (dtype != ATTN_BF16 || (d != 128 && d != 64)) return ATTN_ERR_UNSUPPORTED;
   if (scale <= 0.0f) return ATTN_ERR_UNSUPPORTED;
   if ((long long)N * d * 2 >= (1ll << 31)) return ATTN_ERR_UNSUPPORTED;
   if ((long long)B * Hq * ((N + 255) / 256) > 0x7fffffffll) return ATTN_ERR_UNSUPPORTED;
@@ -108,7 +108,7 @@ int bwd_validate(const void* q, const void* k, const void* v, const void* o, con
 }
 
 int bwd_run(const void* q, const void* k, const void* v, const void* o, const void* dout, const float* lse, void* dq, void* dk,
-            void* dv, float* workspace, int B, int Hq, int Hkv, int N, int causal, float scale, void* stream) {
+            void* dv, float* workspace, int B, int Hq, int Hkv, int N, int d, int causal, float scale, void* stream) {
   AttnBwdParams p;
   p.q = q; p.k = k; p.v = v; p.o = o; p.dout = dout; p.lse = lse;
   p.dq = dq; p.dk = dk; p.dv = dv; p.ws = workspace;
@@ -118,7 +118,7 @@ int bwd_run(const void* q, const void* k, const void* v, const void* o, const vo
   p.causal = causal ? 1 : 0;
   p.scale_log2 = scale * kLog2e;
   p.scale = scale;
-  return attn_bwd_launch_bf16_d128(p, (hipStream_t)stream) == 0 ? ATTN_OK : ATTN_ERR_LAUNCH;
+  return attn_bwd_launch_bf16(p, d, (hipStream_t)stream) == 0 ? ATTN_OK : ATTN_ERR_LAUNCH;
 }
 
 // Scratch memory of attn_bwd_noalloc: the per-row statistics the backward kernels pass from the
@@ -210,7 +210,7 @@ int attn_bwd(const void* q, const void* k, const void* v, const void* o, const v
   if (st != ATTN_OK) return st;
   if (!workspace) return ATTN_ERR_NULL;
   if (misaligned(workspace, 16)) return ATTN_ERR_SHAPE;
-  return bwd_run(q, k, v, o, dout, lse, dq, dk, dv, workspace, B, Hq, Hkv, N, causal, scale, stream);
+  return bwd_run(q, k, v, o, dout, lse, dq, dk, dv, workspace, B, Hq, Hkv, N, d, causal, scale, stream);
 }
 
 int attn_bwd_noalloc(const void* q, const void* k, const void* v, const void* o, const void* dout, const float* lse, void* dq,
@@ -220,7 +220,7 @@ int attn_bwd_noalloc(const void* q, const void* k, const void* v, const void* o,
   if (attn_bwd_workspace_bytes(B, Hq, N) > kScratchBytes) return ATTN_ERR_TOO_LARGE;
   float* const ws = scratch_on_current_device();
   if (!ws) return ATTN_ERR_LAUNCH;
-  return bwd_run(q, k, v, o, dout, lse, dq, dk, dv, ws, B, Hq, Hkv, N, causal, scale, stream);
+  return bwd_run(q, k, v, o, dout, lse, dq, dk, dv, ws, B, Hq, Hkv, N, d, causal, scale, stream);
 }
 
 long long attn_bwd_noalloc_max_workspace_bytes(void) { return kScratchBytes; }

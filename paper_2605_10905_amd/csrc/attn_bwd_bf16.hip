@@ -1,4 +1,4 @@
-// Attention backward, bf16, gfx950 (head dimension 128).
+// Attention backward, bf16, gfx950 (head dimension 128 or 64).
 //
 // The paper lists the backward pass beside the forward among its attention kernels (section
 // 6.1; appendix A, attention shape table, backward rows).  Given Q, K, V, the forward output O
@@ -52,15 +52,23 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
   return __builtin_bit_cast(uint32_t, t);
 }
 
-// Chunk swizzle of a streamed tile with 256-byte rows (16 chunks): XOR with the bit-swapped
-// low four row bits.  Row-wise operand reads (16 lanes, one chunk of 16 consecutive rows) see
-// 16 different values; transposing reads (16 lanes over 4 consecutive rows x 32 bytes, two
-// such groups on neighbouring chunk pairs served together) see the rows in different
-// 64-byte groups.
-__device__ __forceinline__ constexpr int swz_rt(int row) { return ((row & 3) << 2) | ((row >> 2) & 3); }
+// Chunk swizzle of a streamed tile.  256-byte rows (16 chunks): XOR with the bit-swapped low four
+// row bits.  Row-wise operand reads (16 lanes, one chunk of 16 consecutive rows) see 16 different
+// values; transposing reads (16 lanes over 4 consecutive rows x 32 bytes, two such groups on
+// neighbouring chunk pairs served together) see the rows in different 64-byte groups.
+// 128-byte rows (8 chunks, two rows per 256-byte bank line): rows of equal parity share a half
+// line, so the XOR value is built from row bits 1-3: bit 1 selects the 64-byte group (rows r and
+// r + 2, which a transposing read takes together, fall into different groups), bits 2-3 the chunk
+// inside it; 16 consecutive rows then see every (half line, chunk) pair once.
+template <int ROWB>
+__device__ __forceinline__ constexpr int swz_rt(int row) {
+  static_assert(ROWB == 256 || ROWB == 128, "row of 128 or 64 bf16");
+  return ROWB == 256 ? ((row & 3) << 2) | ((row >> 2) & 3) : (((row >> 1) & 1) << 2) | ((row >> 2) & 3);
+}
 
+template <int D_>
 struct BwdCommon {
-  static constexpr int D = 128, BN = 64, NWAVES = 8, BM = NWAVES * 32, NT = NWAVES * 64;
+  static constexpr int D = D_, BN = 64, NWAVES = 8, BM = NWAVES * 32, NT = NWAVES * 64;
   static constexpr int NKK = D / 16, NCB = D / 32, ROWB = D * 2, NCH = ROWB / 16;
   static constexpr int TILEB = BN * ROWB, SUBB = 32 * ROWB, NSLOT = 3;
   static constexpr int T2BASE = NSLOT * TILEB;       // second streamed tensor's slots
@@ -97,9 +105,9 @@ __device__ __forceinline__ void store_transposed(const f32x16 (&acc)[NCB], float
 // =====================================================================================================
 // dQ (and the workspace vectors)
 // =====================================================================================================
-template <bool CAUSAL>
+template <int D, bool CAUSAL>
 __global__ void __launch_bounds__(512, 2) attn_bwd_dq_kernel(const AttnBwdParams p) {
-  using C = BwdCommon;
+  using C = BwdCommon<D>;
   constexpr int NKK = C::NKK, NCB = C::NCB, ROWB = C::ROWB, NCH = C::NCH, TILEB = C::TILEB, SUBB = C::SUBB, NSLOT = C::NSLOT;
   constexpr int NLD = C::NLD, NT = C::NT, BN = C::BN, BM = C::BM;
 
@@ -133,7 +141,7 @@ __global__ void __launch_bounds__(512, 2) attn_bwd_dq_kernel(const AttnBwdParams
     const int s = it * NT + tid;
     const int r = s / NCH, c = s % NCH;
     ld_row[it] = r;
-    ld_off[it] = r * ROWB + ((c ^ swz_rt(r)) << 4);
+    ld_off[it] = r * ROWB + ((c ^ swz_rt<ROWB>(r)) << 4);
   }
   const uint32_t lds_wave = (uint32_t)(uintptr_t)smem + w * 1024;
   auto issue_tile = [&](int j, int slot) __attribute__((always_inline)) {
@@ -180,7 +188,7 @@ __global__ void __launch_bounds__(512, 2) attn_bwd_dq_kernel(const AttnBwdParams
   // ---- LDS read addresses (slot 0, first 32-row block) --------------------------------------------
   uint32_t raddr[NKK];  // row-wise operand: row qi, chunk 2kk + h
 #pragma unroll
-  for (int kk = 0; kk < NKK; ++kk) raddr[kk] = qi * ROWB + (((2 * kk + h) ^ swz_rt(qi)) << 4);
+  for (int kk = 0; kk < NKK; ++kk) raddr[kk] = qi * ROWB + (((2 * kk + h) ^ swz_rt<ROWB>(qi)) << 4);
   uint32_t taddr[NCB][2];  // transposed operand through the transposing load
   {
     const int s = lane & 15, chalf = (lane >> 4) & 1;
@@ -190,7 +198,7 @@ __global__ void __launch_bounds__(512, 2) attn_bwd_dq_kernel(const AttnBwdParams
       for (int e = 0; e < 2; ++e) {
         const int key = 8 * e + 4 * h + (s >> 2);
         const int chunk = cb * 4 + chalf * 2 + ((s & 3) >> 1);
-        taddr[cb][e] = key * ROWB + ((chunk ^ swz_rt(key)) << 4) + ((s & 1) << 3);
+        taddr[cb][e] = key * ROWB + ((chunk ^ swz_rt<ROWB>(key)) << 4) + ((s & 1) << 3);
       }
   }
   auto row_operand = [&](int base, int kk) __attribute__((always_inline)) { return *(LDS_AS bf16x8*)(smem + raddr[kk] + base); };
@@ -291,26 +299,31 @@ __global__ void __launch_bounds__(512, 2) attn_bwd_dq_kernel(const AttnBwdParams
 #ifndef ATTN_BWD_RA
 #define ATTN_BWD_RA 8
 #endif
+template <int D_>
 struct BwdPipe {
-  static constexpr int D = 128, BN = 64, NWAVES = 4, BM = NWAVES * 32, NT = NWAVES * 64;
+  static constexpr int D = D_, BN = 64, NWAVES = 4, BM = NWAVES * 32, NT = NWAVES * 64;
   static constexpr int NKK = D / 16, NCB = D / 32, ROWB = D * 2, NCH = ROWB / 16;
   static constexpr int TILEB = BN * ROWB, SUBB = 32 * ROWB, NSLOT = 4;
   static constexpr int T2BASE = NSLOT * TILEB;
   static constexpr int AUXBASE = 2 * NSLOT * TILEB;
-  static constexpr int NLD = BN * NCH / NT;  // 4
+  static constexpr int NLD = BN * NCH / NT;
   static constexpr int LDS_BYTES = AUXBASE + NSLOT * 512;
-  static constexpr int NM = 32, RA = ATTN_BWD_RA;
+  static constexpr int NS = 2 * NKK;         // score products of a block: S and dP, NKK k-steps each
+  static constexpr int NG = 4 * NCB;         // gradient products of a block: dV and dK, NCB column blocks x 2 k-steps
+  static constexpr int NM = NS + NG;         // 32 (d = 128) or 16 (d = 64)
+  static constexpr int RA = D == 128 ? ATTN_BWD_RA : 4;
+  static_assert(NS == NG && RA % 4 == 0 && RA <= NS && NM % 4 == 0, "schedule shape");
   // slot p of a step: the first RA MFMAs are gradient products (their operands were requested by
   // the previous step, from a tile that is certainly resident), then score and gradient products
   // alternate, and the last RA are score products
   static constexpr bool is_score(int p) {
     if (p < RA) return false;
-    const int q = p - RA, npairs = 16 - RA;
+    const int q = p - RA, npairs = NS - RA;
     return q < 2 * npairs ? (q & 1) == 0 : true;
   }
   static constexpr int index(int p) {
     if (p < RA) return p;
-    const int q = p - RA, npairs = 16 - RA;
+    const int q = p - RA, npairs = NS - RA;
     if (q < 2 * npairs) return (q & 1) == 0 ? q / 2 : RA + q / 2;
     return npairs + (q - 2 * npairs);
   }
@@ -323,9 +336,9 @@ struct BwdPipe {
   static constexpr int aslot(int a) { return vslot(4 * a) - 6 > 0 ? vslot(4 * a) - 6 : 0; }  // slot that reads the statistics of rows 4a..4a+3
 };
 
-template <bool CAUSAL>
+template <int D, bool CAUSAL>
 __global__ void __launch_bounds__(256, 1) attn_bwd_dkv_pipe_kernel(const AttnBwdParams p) {
-  using C = BwdPipe;
+  using C = BwdPipe<D>;
   constexpr int NKK = C::NKK, NCB = C::NCB, ROWB = C::ROWB, NCH = C::NCH, TILEB = C::TILEB, SUBB = C::SUBB, NSLOT = C::NSLOT;
   constexpr int NLD = C::NLD, NT = C::NT, BN = C::BN, BM = C::BM, NM = C::NM, RA = C::RA;
 
@@ -358,7 +371,7 @@ __global__ void __launch_bounds__(256, 1) attn_bwd_dkv_pipe_kernel(const AttnBwd
     const int s = it * NT + tid;
     const int r = s / NCH, c = s % NCH;
     ld_row[it] = r;
-    ld_off[it] = r * ROWB + ((c ^ swz_rt(r)) << 4);
+    ld_off[it] = r * ROWB + ((c ^ swz_rt<ROWB>(r)) << 4);
   }
   const uint32_t lds_base = (uint32_t)(uintptr_t)smem;
   const uint32_t lds_wave = lds_base + w * 1024;
@@ -427,7 +440,7 @@ __global__ void __launch_bounds__(256, 1) attn_bwd_dkv_pipe_kernel(const AttnBwd
   uint32_t raddr[2][NKK];
 #pragma unroll
   for (int kk = 0; kk < NKK; ++kk) {
-    raddr[0][kk] = ki * ROWB + (((2 * kk + h) ^ swz_rt(ki)) << 4);
+    raddr[0][kk] = ki * ROWB + (((2 * kk + h) ^ swz_rt<ROWB>(ki)) << 4);
     raddr[1][kk] = raddr[0][kk] + C::T2BASE;
   }
   uint32_t taddr[2][NCB][2];
@@ -439,7 +452,7 @@ __global__ void __launch_bounds__(256, 1) attn_bwd_dkv_pipe_kernel(const AttnBwd
       for (int e = 0; e < 2; ++e) {
         const int row = 8 * e + 4 * h + (s >> 2);
         const int chunk = cb * 4 + chalf * 2 + ((s & 3) >> 1);
-        taddr[0][cb][e] = row * ROWB + ((chunk ^ swz_rt(row)) << 4) + ((s & 1) << 3);
+        taddr[0][cb][e] = row * ROWB + ((chunk ^ swz_rt<ROWB>(row)) << 4) + ((s & 1) << 3);
         taddr[1][cb][e] = taddr[0][cb][e] + C::T2BASE;
       }
   }
@@ -455,11 +468,11 @@ __global__ void __launch_bounds__(256, 1) attn_bwd_dkv_pipe_kernel(const AttnBwd
     return __builtin_bit_cast(u32x4, av);
   };
   // operand of gradient product i of the block at `off`: dV^T += dO^T P (even i), dK^T += Q^T dS (odd i)
-  auto grad_operand = [&](int off, int i) __attribute__((always_inline)) { return tr_operand((i & 1) ? 0 : 1, off, (i >> 1) & 3, i >> 3); };
+  auto grad_operand = [&](int off, int i) __attribute__((always_inline)) { return tr_operand((i & 1) ? 0 : 1, off, (i >> 1) % NCB, (i >> 1) / NCB); };
   // operand of score product i of the block at `off`: S += Q K^T (even i), dP += dO V^T (odd i)
   auto score_operand = [&](int off, int i) __attribute__((always_inline)) { return row_operand(i & 1, off, i >> 1); };
   auto grad_mfma = [&](int i, u32x4 o, const u32x4 (&pp)[2], const u32x4 (&pd)[2]) __attribute__((always_inline)) {
-    const int cb = (i >> 1) & 3, kc = i >> 3;
+    const int cb = (i >> 1) % NCB, kc = (i >> 1) / NCB;
     if (i & 1) acc_dk[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, o), __builtin_bit_cast(bf16x8, pd[kc]), acc_dk[cb], 0, 0, 0);
     else acc_dv[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, o), __builtin_bit_cast(bf16x8, pp[kc]), acc_dv[cb], 0, 0, 0);
   };
@@ -597,7 +610,7 @@ __global__ void __launch_bounds__(256, 1) attn_bwd_dkv_pipe_kernel(const AttnBwd
   {
     const int last = ((nt - 1) & 3) * TILEB + SUBB;
 #pragma unroll
-    for (int i = RA; i < 16; ++i) grad_mfma(i, grad_operand(last, i), ppb, pdb);
+    for (int i = RA; i < C::NG; ++i) grad_mfma(i, grad_operand(last, i), ppb, pdb);
 #pragma unroll
     for (int i = 0; i < RA; ++i) grad_mfma(i, pre[i], ppb, pdb);
   }
@@ -610,15 +623,21 @@ __global__ void __launch_bounds__(256, 1) attn_bwd_dkv_pipe_kernel(const AttnBwd
 
 }  // namespace
 
-int attn_bwd_launch_bf16_d128(const AttnBwdParams& p, hipStream_t stream) {
+int attn_bwd_launch_bf16(const AttnBwdParams& p, int d, hipStream_t stream) {
   const int grid_q = p.B * p.Hq * p.T;
   const int grid_f = p.B * p.Hkv * ((p.N + 127) / 128);
-  if (p.causal) {
-    hipLaunchKernelGGL((attn_bwd_dq_kernel<true>), dim3(grid_q), dim3(512), 0, stream, p);
-    hipLaunchKernelGGL((attn_bwd_dkv_pipe_kernel<true>), dim3(grid_f), dim3(256), 0, stream, p);
-  } else {
-    hipLaunchKernelGGL((attn_bwd_dq_kernel<false>), dim3(grid_q), dim3(512), 0, stream, p);
-    hipLaunchKernelGGL((attn_bwd_dkv_pipe_kernel<false>), dim3(grid_f), dim3(256), 0, stream, p);
-  }
+  auto launch = [&](auto dtag) {
+    constexpr int D = decltype(dtag)::value;
+    if (p.causal) {
+      hipLaunchKernelGGL((attn_bwd_dq_kernel<D, true>), dim3(grid_q), dim3(512), 0, stream, p);
+      hipLaunchKernelGGL((attn_bwd_dkv_pipe_kernel<D, true>), dim3(grid_f), dim3(256), 0, stream, p);
+    } else {
+      hipLaunchKernelGGL((attn_bwd_dq_kernel<D, false>), dim3(grid_q), dim3(512), 0, stream, p);
+      hipLaunchKernelGGL((attn_bwd_dkv_pipe_kernel<D, false>), dim3(grid_f), dim3(256), 0, stream, p);
+    }
+  };
+  if (d == 128) launch(ic<128>{});
+  else if (d == 64) launch(ic<64>{});
+  else return -1;
   return (int)hipGetLastError();
 }

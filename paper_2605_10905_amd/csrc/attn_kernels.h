@@ -20,7 +20,7 @@ struct AttnParams {
 // persistent bf16 forward (d = 64 or 128): `workgroups` resident workgroups drain the tile queue
 int attn_fwd_bf16_persistent_launch(const AttnParams& p, int d, int workgroups, hipStream_t stream);
 
-// backward pass (bf16, head dimension 128)
+// backward pass (bf16, head dimension 128 or 64)
 struct AttnBwdParams {
   const void* q;
   const void* k;
@@ -39,7 +39,7 @@ struct AttnBwdParams {
   float scale_log2;  // scale * log2(e)
   float scale;
 };
-int attn_bwd_launch_bf16_d128(const AttnBwdParams& p, hipStream_t stream);
+int attn_bwd_launch_bf16(const AttnBwdParams& p, int d, hipStream_t stream);  // d = 128 or 64
 
 struct AttnVariant {
   const char* name;

@@ -178,7 +178,7 @@ def test_backward_and_persistent_validation_without_a_device(A):
 
     assert bwd(q=None) == 1 and bwd(ws=None) == 1
     assert bwd(N=0) == 2 and bwd(Hq=3, Hkv=2) == 2 and bwd(ws=p + 4) == 2
-    assert bwd(d=64) == 4                      # the backward covers head dimension 128 only
+    assert bwd(d=96) == 4 and bwd(d=256) == 4  # the backward covers head dimensions 128 and 64
     assert bwd(dtype=1) in (3, 4)              # and bf16 only
     assert A.attn_bwd_workspace_bytes(2, 32, 8192) == 2 * 32 * 2 * 8192 * 4
     assert A.attn_bwd_workspace_bytes(1, 1, 1) == 2 * 64 * 4 and A.attn_bwd_workspace_bytes(0, 1, 1) == 0
@@ -188,7 +188,7 @@ def test_backward_and_persistent_validation_without_a_device(A):
     def bwd_na(q=p, d=128, dtype=0, N=8, Hq=2, Hkv=1, B=1):
         return A.attn_bwd_noalloc(q, p, p, p, p, p, p, p, p, B, Hq, Hkv, N, d, 0, 0.5, dtype, stream=0, check=False)
 
-    assert bwd_na(q=None) == 1 and bwd_na(N=0) == 2 and bwd_na(Hq=3, Hkv=2) == 2 and bwd_na(d=64) == 4
+    assert bwd_na(q=None) == 1 and bwd_na(N=0) == 2 and bwd_na(Hq=3, Hkv=2) == 2 and bwd_na(d=96) == 4
     cap = A.attn_bwd_noalloc_max_workspace_bytes()
     assert cap == 32 << 20
     assert A.attn_bwd_workspace_bytes(4, 64, 16384) == cap and A.attn_bwd_workspace_bytes(4, 64, 16385) > cap

@@ -1,4 +1,4 @@
-"""GPU parity of the attention backward pass (bf16, head dimension 128): the HIP path, called
+"""GPU parity of the attention backward pass (bf16, head dimension 128 or 64): the HIP path, called
 through the C ABI on the forward's own outputs, against the float64 CPU oracle of the
 gradients on the same seeded inputs."""
 import numpy as np
@@ -11,12 +11,15 @@ from tests import gpu_util as gu
 pytestmark = pytest.mark.gpu
 
 
-def _case(ci, B, Hq, Hkv, N, causal=None, seed=None):
+def _case(ci, B, Hq, Hkv, N, causal=None, seed=None, d=None):
     cfg = dict(wl.CONFIGS[ci])
     if causal is not None:
         cfg["causal"] = causal
     if seed is not None:
         cfg["seed"] = seed
+    if d is not None:
+        cfg["d"] = d
+        cfg["scale"] = 1.0 / float(np.sqrt(d))
     inp = wl.make_inputs(cfg, B=B, Hq=Hq, Hkv=Hkv, N=N)
     return cfg, inp, wl.make_dout(cfg, B=B, Hq=Hq, N=N)
 
@@ -50,6 +53,25 @@ def test_bwd_edge_lengths(N, causal):
     print(f"bwd edge N={N} causal={causal}", flush=True)
     dq, dk, dv, _, _ = gu.run_gpu_bwd(inp, dob)
     gu.check_bwd_full(inp, dob, dq, dk, dv, f"bwd edge N={N} causal={causal}")
+
+
+# head dimension 64: the same kernels with half the k-steps and column blocks and the 128-byte-row
+# swizzle of the streamed tiles
+@pytest.mark.parametrize("N", [1, 33, 64, 65, 127, 128, 129, 255, 257, 513])
+@pytest.mark.parametrize("causal", [False, True])
+def test_bwd_d64_edge_lengths(N, causal):
+    cfg, inp, dob = _case(1, 1, 2, 1, N, causal=causal, seed=911 + N, d=64)
+    print(f"bwd d64 edge N={N} causal={causal}", flush=True)
+    dq, dk, dv, _, _ = gu.run_gpu_bwd(inp, dob)
+    gu.check_bwd_full(inp, dob, dq, dk, dv, f"bwd d64 edge N={N} causal={causal}")
+
+
+@pytest.mark.parametrize("ci,B,Hq,Hkv,N", [(1, 1, 2, 2, 2048), (2, 2, 2, 2, 1531), (3, 1, 8, 2, 1024), (3, 2, 8, 1, 777)])
+def test_bwd_d64_reduced_configs(ci, B, Hq, Hkv, N):
+    cfg, inp, dob = _case(ci, B, Hq, Hkv, N, d=64)
+    print(f"bwd d64 config{ci + 1} reduced B={B} Hq={Hq} Hkv={Hkv} N={N} causal={cfg['causal']}", flush=True)
+    dq, dk, dv, _, _ = gu.run_gpu_bwd(inp, dob)
+    print(gu.check_bwd_full(inp, dob, dq, dk, dv, f"bwd d64 cfg{ci + 1} N={N}"), flush=True)
 
 
 def _bits(x):
@@ -102,8 +124,8 @@ def test_bwd_rejects_what_it_does_not_cover():
     lse = torch.zeros(2 * 64, dtype=torch.float32, device="cuda")
     ws = torch.zeros(A.attn_bwd_workspace_bytes(1, 2, 64) // 4, dtype=torch.float32, device="cuda")
     common = dict(stream=None, check=False)
-    # head dimension 64 and fp8 have no backward kernel
-    assert A.attn_bwd(t, t, t, t, t, lse, t, t, t, ws, 1, 2, 2, 64, 64, 0, 0.125, A.ATTN_BF16, **common) != 0
+    # other head dimensions than 128 and 64, and fp8, have no backward kernel
+    assert A.attn_bwd(t, t, t, t, t, lse, t, t, t, ws, 1, 2, 2, 64, 32, 0, 0.125, A.ATTN_BF16, **common) != 0
     assert A.attn_bwd(t, t, t, t, t, lse, t, t, t, ws, 1, 2, 2, 64, 128, 0, 0.125, A.ATTN_FP8_E4M3, **common) != 0
     assert A.attn_bwd(t, t, t, t, t, lse, t, t, t, None, 1, 2, 2, 64, 128, 0, 0.125, A.ATTN_BF16, **common) != 0
 
