@@ -265,7 +265,7 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_sp_kernel(const AttnParams p)
   };
   auto lds_ops_done = [&]() __attribute__((always_inline)) { __builtin_amdgcn_s_waitcnt(0xC07F); };  // lgkmcnt(0)
 
-  // ---- first requests of a tile: key tile 0, bundles 0 and 1, and the Q operand ------------------
+  // ---- first requests of a tile: key tile 0, bundle 0 and the Q operand ---------------------------
   // bundle b = key tile b+1 (the last tile again if there is none) and value tile b.
   // Q is the B operand of S^T = K Q^T: bf16: lane (qi,h) holds Q[row][16kk + 8h .. +7];
   // fp8: Q[row][64kk + 32h .. +31].
@@ -284,12 +284,6 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_sp_kernel(const AttnParams p)
         qf[kk] = i32x8{(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3], (int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
       } else {
         qf[kk] = *(const bf16x8*)(src + kk * 32);
-      }
-    }
-    if constexpr (!FP8) {
-      if (nt > 1) {
-        issue_k(min(2, nt - 1), 1);
-        issue_v(1, 1);
       }
     }
   };
@@ -632,13 +626,20 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_sp_kernel(const AttnParams p)
       }
       if (nt > 2) issue_v(2, 0);
     } else {
-      // key tile 0 (and Q) have landed once only the bundle loads issued after them are outstanding
-      if (nt > 1) ATTN_WAIT_VMCNT(4 * NLD);
-      else ATTN_WAIT_VMCNT(2 * NLD);
+      // Q is in registers from here on.  The compiler waits for Q with the counter that the
+      // direct-to-LDS loads share and cannot see them, so this is a wait for every load issued
+      // so far: bundle 1 is therefore requested only behind the barrier.
+      ATTN_WAIT_VMCNT(0);
   #pragma unroll
-      for (int kk = 0; kk < NKQ; ++kk) asm volatile("" ::"v"(qf[kk]));  // Q is in registers from here on
+      for (int kk = 0; kk < NKQ; ++kk) asm volatile("" ::"v"(qf[kk]));
     }
     attn_wg_barrier();
+    if constexpr (!FP8) {
+      if (nt > 1) {
+        issue_k(min(2, nt - 1), 1);
+        issue_v(1, 1);
+      }
+    }
     if (wave_valid) {
       qk_block(s_b, (NSLOT - 1) * KTILEB);             // S(0)
       softmax_block(s_b, p_b, p_a, 0, needs_mask(0));  // P(0) -> p_b (nothing pending yet)
