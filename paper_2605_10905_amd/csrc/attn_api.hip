@@ -10,7 +10,8 @@
 #include "tile_map.h"
 
 constexpr long long kScratchBytes = 32ll << 20;
-static __device__ __align__(256) unsigned char scratch[kScratchBytes];  // see scratch_on_current_device()
+// (no kernel names the array, so it is marked used: it must stay in the code object)
+__attribute__((used)) static __device__ __align__(256) unsigned char scratch[kScratchBytes];  // see scratch_on_current_device()
 
 namespace {
 
