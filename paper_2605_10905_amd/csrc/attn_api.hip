@@ -10,8 +10,10 @@
 #include "tile_map.h"
 
 constexpr long long kScratchBytes = 32ll << 20;
-// (no kernel names the array, so it is marked used: it must stay in the code object)
-__attribute__((used)) static __device__ __align__(256) unsigned char scratch[kScratchBytes];  // see scratch_on_current_device()
+// A plain static device array: the compiler keeps a static device variable that host code names
+// and makes it visible to the runtime under its mangled name.  (With __attribute__((used)) added
+// the runtime could no longer find it: hipGetSymbolAddress aborted the process.)
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];  // see scratch_on_current_device()
 
 namespace {
 
