@@ -88,6 +88,7 @@ int run(const void* q, const void* k, const void* v, void* o, float* lse, int B,
   p.causal = causal ? 1 : 0;
   p.scale_log2 = scale * qk_descale * kLog2e;
   p.out_scale = v_descale;
+  p.map = attn_tile_map_make(B, Hq, Hkv, p.T, p.causal);
   const long long grid = (long long)B * Hq * p.T;
   if (grid <= 0 || grid > 0x7fffffffll) return ATTN_ERR_UNSUPPORTED;
   const int err = a->launch(p, (int)grid, (hipStream_t)stream);
@@ -195,6 +196,7 @@ int attn_fwd_persistent(const void* q, const void* k, const void* v, void* o, fl
   p.causal = causal ? 1 : 0;
   p.scale_log2 = scale * kLog2e;
   p.out_scale = 1.0f;
+  p.map = attn_tile_map_make(B, Hq, Hkv, p.T, p.causal);
   const long long total = (long long)B * Hq * p.T;
   if (total > 0x0fffffffll) return ATTN_ERR_UNSUPPORTED;
   p.queue = (int*)queue;

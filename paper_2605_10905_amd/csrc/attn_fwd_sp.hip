@@ -147,7 +147,7 @@ __global__ void __launch_bounds__(512, 2) attn_fwd_sp_kernel(const AttnParams p)
   int kv_end, nt;                   // keys the workgroup visits; 64-key tiles = bundles
   int qrow, limit, wlast;           // this lane's query row, its last visible key, the wave's last row
   auto set_tile = [&](int wg) __attribute__((always_inline)) {
-    const AttnTileCoord tc = attn_tile_coord_impl(wg, p.B, p.Hq, p.Hkv, p.T, CAUSAL ? 1 : 0);
+    const AttnTileCoord tc = attn_tile_coord_map(wg, p.map);
     tile_b = tc.b;
     tile_hq = tc.hq;
     const int hk = tc.hq / G;

@@ -2,6 +2,8 @@
 #pragma once
 #include <hip/hip_runtime.h>
 
+#include "tile_map.h"
+
 struct AttnParams {
   const void* q;
   const void* k;
@@ -15,6 +17,7 @@ struct AttnParams {
   float out_scale;   // multiplies O in the epilogue (v_descale and P scaling for fp8; 1 for bf16)
   int* queue = nullptr;  // persistent launch only: 8 tile-list counters, 32 ints apart
   int total = 0;         // persistent launch only: number of query tiles = B * Hq * T
+  AttnTileMap map;       // attn_tile_map_make(B, Hq, Hkv, T, causal): workgroup id -> (batch, head, tile)
 };
 
 // persistent bf16 forward (d = 64 or 128): `workgroups` resident workgroups drain the tile queue

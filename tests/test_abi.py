@@ -3,6 +3,8 @@ header declares, rejects bad arguments before touching a device, and its work
 decomposition is a bijection that keeps K/V sharers on one XCD."""
 import ctypes
 import os
+
+import numpy as np
 import re
 
 import pytest
@@ -108,6 +110,42 @@ def test_tile_map_is_a_bijection_and_xcd_local(A, B, Hq, Hkv, N, BM, causal):
         assert all(t == T - 1 for t in first_t_of_head.values())  # heaviest tile first
     with pytest.raises(A.AttnError):
         A.attn_tile_coord(n, B, Hq, Hkv, N, BM, causal)
+
+
+def _tile_coord_by_plain_division(wg, B, Hq, Hkv, T, causal, batch_wgs=64):
+    """The tile order written with Python's integer division (the library divides by the launch's
+    constants with a multiply-high and one correction)."""
+    G, groups, W = Hq // Hkv, B * Hkv, (Hq // Hkv) * T
+    lists = 8 if groups % 8 == 0 else 1
+    xcd, s = (wg % 8, wg // 8) if lists == 8 else (0, wg)
+    if causal:
+        gx = groups // lists
+        pb = min((batch_wgs * (8 // lists) + W - 1) // W, gx)
+        batch, r = divmod(s, pb * W)
+        nb = min(gx - batch * pb, pb)
+        tt, rem = divmod(r, nb * G)
+        gl, hg = batch * pb + rem // G, rem % G
+    else:
+        gl, inner = divmod(s, W)
+        tt, hg = divmod(inner, G)
+    group = gl * lists + xcd
+    return group // Hkv, (group % Hkv) * G + hg, (T - 1 - tt) if causal else tt
+
+
+def test_tile_map_equals_its_definition_by_plain_division(A):
+    rng = np.random.default_rng(77)
+    shapes = [(1, 1, 1, 1), (2, 32, 32, 8192), (4, 64, 8, 4096), (3, 5, 5, 13100), (1, 12, 4, 16450), (7, 3, 1, 300), (8, 9, 3, 2000),
+              (5, 16, 2, 70000), (16, 1, 1, 257)]
+    shapes += [(int(rng.integers(1, 9)), int(g * k), int(k), int(rng.integers(1, 40000)))
+               for g, k in zip(rng.integers(1, 9, 12), rng.integers(1, 9, 12))]
+    for B, Hq, Hkv, N in shapes:
+        T = (N + 255) // 256
+        n = A.attn_num_workgroups(B, Hq, N, 256)
+        ids = set(range(min(n, 300))) | set(range(max(0, n - 300), n)) | {int(x) for x in rng.integers(0, n, 400)}
+        for causal in (False, True):
+            for wg in ids:
+                assert tuple(A.attn_tile_coord(wg, B, Hq, Hkv, N, 256, causal)) == _tile_coord_by_plain_division(wg, B, Hq, Hkv, T, causal), \
+                    (wg, B, Hq, Hkv, N, causal)
 
 
 def test_no_product_code_imports_the_oracle():
