@@ -359,6 +359,19 @@ def test_causal_list_walking_launch(B, Hq, Hkv, N, d, ci):
     if inp["dtype"] == "bf16":  # (the queue launch takes bf16 inputs only)
         o2, lse2 = _run_persistent(inp, dev)
         assert torch.equal(o.view(torch.int16), o2.view(torch.int16)) and torch.equal(lse, lse2)
+        # the same launch captured in a graph (its host side only reads device attributes) and replayed
+        o3, lse3 = torch.empty_like(o), torch.empty_like(lse)
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            A.attn_fwd(dev["q"], dev["k"], dev["v"], o3, lse3, B, Hq, Hkv, N, d, True, inp["scale"], A.ATTN_BF16)
+        for rep in range(2):
+            o3.fill_(float("nan"))
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(o3.view(torch.int16), o.view(torch.int16)) and torch.equal(lse3, lse), f"replay {rep}"
 
 
 # ---- stream capture: nothing in the library allocates, synchronises or uses a memset node --------------
