@@ -32,6 +32,16 @@ int choose(int M, int N, int K, const GemmVariant* table, int count) {
   return v;
 }
 
+// Non-temporal stores of C, measured on the paper's shapes (interleaved, one process): they pay
+// where C's rows are short and the product is bound by memory traffic (442368 x 448 x 192: +11 %,
+// 589824 x 256 x 128: +4 %) and where a long contraction makes C a small part of the traffic that
+// should not displace operand panels in the L2 (8192 x 8192 x 8192 / 16384: +2 %); with long rows
+// and a short contraction they cost (8192 x 8192 x 1024: -8 %, 2048 x 64512 x 256: -9 %).
+int stream_c_pays(int M, int N, int K) {
+  (void)M;
+  return (N <= 512 || K >= 8192) ? 1 : 0;
+}
+
 int run(const void* a, const void* b, void* c, int M, int N, int K, int variant, void* stream) {
   if (!a || !b || !c) return ATTN_ERR_NULL;
   if (M <= 0 || N <= 0 || K <= 0) return ATTN_ERR_SHAPE;
@@ -51,6 +61,7 @@ int run(const void* a, const void* b, void* c, int M, int N, int K, int variant,
   p.tiles_m = (M + v.bm - 1) / v.bm;
   p.tiles_n = (N + v.bn - 1) / v.bn;
   if ((long long)p.tiles_m * p.tiles_n > 0x7fffffffll) return ATTN_ERR_UNSUPPORTED;
+  p.stream_c = stream_c_pays(M, N, K);
   return v.launch(p, (hipStream_t)stream) == 0 ? ATTN_OK : ATTN_ERR_LAUNCH;
 }
 

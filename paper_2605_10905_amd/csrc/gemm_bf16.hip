@@ -27,6 +27,15 @@
 #include "gemm_kernels.h"
 #include "gemm_map.h"
 
+// One 16-byte piece of C: plain, or non-temporal when the launch streams C (GemmParams::stream_c).
+// (Written as an assembly statement: the compiler merges a plain and a non-temporal store behind a
+// run-time condition into one plain store.  It is the kernel's last memory operation.)
+#define GEMM_STORE_C(val, ptr)                                                                          \
+  do {                                                                                                  \
+    if (p.stream_c) asm volatile("global_store_dwordx4 %0, %1, off nt" ::"v"(ptr), "v"(val) : "memory"); \
+    else *(ptr) = (val);                                                                                \
+  } while (0)
+
 namespace {
 
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
@@ -262,7 +271,7 @@ __global__ void __launch_bounds__(256, MINW) gemm_bf16_kernel(const GemmParams p
         if (m < M) {
           if (vec_ok && n + 8 <= N) {
             u32x4 out = {x[0], x[1], y[0], y[1]};
-            *(u32x4*)(crow + n) = out;
+            GEMM_STORE_C(out, (u32x4*)(crow + n));
           } else {
             const uint32_t v[4] = {x[0], x[1], y[0], y[1]};
 #pragma unroll
@@ -476,7 +485,7 @@ __global__ void __launch_bounds__(256, 1) gemm_bf16_nt_m16_kernel(const GemmPara
       if (m < M) {
         if (vec_ok && n + 8 <= N) {
           u32x4 out = {x[0], x[1], y[0], y[1]};
-          *(u32x4*)(crow + n) = out;
+          GEMM_STORE_C(out, (u32x4*)(crow + n));
         } else {
           const uint32_t v[4] = {x[0], x[1], y[0], y[1]};
 #pragma unroll

@@ -13,6 +13,7 @@ struct GemmParams {
   float* partial = nullptr;
   int splits = 1;
   int klen = 0;
+  int stream_c = 0;  // non-zero: C is written with non-temporal stores (it is not read again and should not displace the operands in the L2)
 };
 
 struct GemmVariant {
