@@ -32,14 +32,15 @@ int choose(int M, int N, int K, const GemmVariant* table, int count) {
   return v;
 }
 
-// Non-temporal stores of C, measured on the paper's shapes (interleaved, one process): they pay
-// where C's rows are short and the product is bound by memory traffic (442368 x 448 x 192: +11 %,
-// 589824 x 256 x 128: +4 %) and where a long contraction makes C a small part of the traffic that
-// should not displace operand panels in the L2 (8192 x 8192 x 8192 / 16384: +2 %); with long rows
-// and a short contraction they cost (8192 x 8192 x 1024: -8 %, 2048 x 64512 x 256: -9 %).
+// Non-temporal stores of C in gemm_bf16_nt, measured on the paper's shapes (interleaved, one
+// process): they pay where C's rows are short and the product is bound by memory traffic (442368 x
+// 448 x 192: +11 %, 589824 x 256 x 128: +3 %) and where a long contraction makes C a small part of
+// the traffic that should not displace operand panels in the L2 (8192 x 8192 x 8192 / 16384: +3 %);
+// elsewhere they cost (8192 x 8192 x 1024: -8 %, 2048 x 64512 x 256: -9 %, 589824 x 512 x 2048:
+// -5 %), and in gemm_bf16_nn they cost at every size tried (-2 .. -3 %), so that entry keeps plain stores.
 int stream_c_pays(int M, int N, int K) {
   (void)M;
-  return (N <= 512 || K >= 8192) ? 1 : 0;
+  return ((N <= 512 && K <= 256) || K >= 8192) ? 1 : 0;
 }
 
 int run(const void* a, const void* b, void* c, int M, int N, int K, int variant, void* stream) {
